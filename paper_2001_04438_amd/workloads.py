@@ -1,0 +1,115 @@
+"""Seeded synthetic inputs shaped like the paper's workloads.
+
+Holds only random-number recipes and storage-format conversion: none of the
+softmax arithmetic.  Both the HIP path's tests/bench and the oracle's tests are
+fed from here, so the two sides always see the same numbers.
+
+The paper benchmarks random arrays of a given length (Section 6.2) and
+motivates the sizes with the class counts of public datasets (Table 1); no
+dataset content is used.  Five named workloads follow the benchmark
+configurations of this build:
+
+  cfg1  single fp32 vector, N = 4096, U[-10, 10]; variant with the overflow
+        probes x[0] = +1e4, x[1] = -1e4
+  cfg2  1024 rows x 32768, fp32, Normal(0, sd 4)
+  cfg3  64 rows x 1,000,000, fp32, 8 * Normal(0, 1) + per-row offset U[-50, 50]
+  cfg4  single fp32 vector, N = 2^28, U[-100, 100] with 0.1 % of the entries
+        replaced by U[500, 1000]
+  cfg5  4096 rows x 21846, bf16, 30 * Normal(0, 1)
+
+Every generator draws from numpy's PCG64 with seed BASE_SEED + cfg, in blocks of
+BLOCK elements in row-major order (float64 draws, then cast to fp32), so the
+values depend only on the seed and the requested shape.  Smaller shapes of the
+same recipe are used where the oracle has to finish in seconds.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+BASE_SEED = 200104438
+BLOCK = 1 << 22
+
+SHAPES = {
+    "cfg1": (1, 4096),
+    "cfg2": (1024, 32768),
+    "cfg3": (64, 1_000_000),
+    "cfg4": (1, 1 << 28),
+    "cfg5": (4096, 21846),
+}
+DTYPES = {"cfg1": "f32", "cfg2": "f32", "cfg3": "f32", "cfg4": "f32", "cfg5": "bf16"}
+
+
+def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """Round fp32 to bfloat16 (round-to-nearest-even), returned as uint16 bit patterns."""
+    w = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    rounding = ((w >> 16) & 1) + np.uint32(0x7FFF)
+    return ((w + rounding) >> 16).astype(np.uint16)
+
+
+def bf16_bits_to_f32(h: np.ndarray) -> np.ndarray:
+    """Widen bfloat16 bit patterns to the fp32 values they denote (exact)."""
+    return (np.ascontiguousarray(h, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
+def _rng(cfg_index: int) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64(BASE_SEED + cfg_index))
+
+
+def _blocks(total: int):
+    done = 0
+    while done < total:
+        c = min(BLOCK, total - done)
+        yield done, c
+        done += c
+
+
+def cfg1(n: int = 4096, probes: bool = False) -> np.ndarray:
+    rng = _rng(1)
+    x = (-10.0 + 20.0 * rng.random(n)).astype(np.float32).reshape(1, n)
+    if probes:
+        x[0, 0] = np.float32(1e4)
+        x[0, 1] = np.float32(-1e4)
+    return x
+
+
+def cfg2(rows: int = 1024, n: int = 32768) -> np.ndarray:
+    rng = _rng(2)
+    out = np.empty(rows * n, dtype=np.float32)
+    for lo, c in _blocks(rows * n):
+        out[lo:lo + c] = (4.0 * rng.standard_normal(c)).astype(np.float32)
+    return out.reshape(rows, n)
+
+
+def cfg3(rows: int = 64, n: int = 1_000_000) -> np.ndarray:
+    rng = _rng(3)
+    off = (-50.0 + 100.0 * rng.random(rows)).astype(np.float32)
+    out = np.empty(rows * n, dtype=np.float32)
+    for lo, c in _blocks(rows * n):
+        out[lo:lo + c] = (8.0 * rng.standard_normal(c)).astype(np.float32)
+    out = out.reshape(rows, n)
+    out += off[:, None]  # fp32 addition: the stored input is fl32(fl32(8 z) + off_r)
+    return out
+
+
+def cfg4(n: int = 1 << 28) -> np.ndarray:
+    rng = _rng(4)
+    out = np.empty(n, dtype=np.float32)
+    for lo, c in _blocks(n):
+        base = -100.0 + 200.0 * rng.random(c)
+        is_outlier = rng.random(c) < 0.001
+        outlier = 500.0 + 500.0 * rng.random(c)
+        out[lo:lo + c] = np.where(is_outlier, outlier, base).astype(np.float32)
+    return out.reshape(1, n)
+
+
+def cfg5(rows: int = 4096, n: int = 21846) -> np.ndarray:
+    """Returns bf16 bit patterns (uint16)."""
+    rng = _rng(5)
+    out = np.empty(rows * n, dtype=np.uint16)
+    for lo, c in _blocks(rows * n):
+        out[lo:lo + c] = f32_to_bf16_bits((30.0 * rng.standard_normal(c)).astype(np.float32))
+    return out.reshape(rows, n)
+
+
+def make(name: str, **kw) -> np.ndarray:
+    return {"cfg1": cfg1, "cfg2": cfg2, "cfg3": cfg3, "cfg4": cfg4, "cfg5": cfg5}[name](**kw)
