@@ -1,0 +1,151 @@
+/*
+ * softmax_tp: Two-Pass softmax (arXiv 2001.04438) and its Three-Pass baselines for
+ * AMD MI355X (gfx950), as a C ABI.
+ *
+ * Every entry point computes, for each of `rows` independent vectors of `n`
+ * elements stored contiguously (row-major, row pitch = n elements),
+ *
+ *        y[r, i] = exp(x[r, i]) / sum_k exp(x[r, k])            (Section 1)
+ *
+ * Common conventions
+ *   x, y     DEVICE pointers.  x is never written.  y == x (exact aliasing) is
+ *            allowed; any other overlap is undefined.  Pointers need only be
+ *            aligned to the element size; when x and y are congruent modulo 16
+ *            bytes the kernels move 128 bits per lane, otherwise they fall back
+ *            to element-wise accesses (same results, lower bandwidth).
+ *   rows, n  rows == 0 or n == 0 is a successful no-op.
+ *   stream   a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *            enqueued and the call returns; nothing is synchronised and nothing
+ *            is copied to the host.  The caller keeps x and y alive until the
+ *            stream has finished.
+ *   inputs   finite values.  Full accuracy (max relative error 4e-6 for fp32
+ *            I/O) holds for |x| <= 1e5; see the Two-Pass entry for larger
+ *            magnitudes.  A NaN anywhere in a row makes that row's outputs NaN;
+ *            infinities are not supported.
+ *   return   0 on success; a negative TP_ERR_* code for an invalid argument,
+ *            detected before any GPU call is made; a positive value is the
+ *            hipError_t of a failed allocation or launch.
+ *   memory   long rows are cut into chunks whose partial results live in a small
+ *            workspace owned by the library (a few KB to a few hundred KB per
+ *            stream), allocated on first use and kept; softmax_tp_release()
+ *            frees it.  The library allocates nothing else.
+ */
+#ifndef SOFTMAX_TP_H
+#define SOFTMAX_TP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TP_API __attribute__((visibility("default")))
+
+#define TP_OK 0
+#define TP_ERR_NULL (-1)      /* x or y is NULL while rows * n > 0 (or an out-pointer is NULL) */
+#define TP_ERR_NEGATIVE (-2)  /* rows < 0 or n < 0 */
+#define TP_ERR_TOO_LARGE (-3) /* rows * n * element size overflows, or rows / chunks exceed the grid limit */
+#define TP_ERR_ALIGN (-4)     /* a pointer is not aligned to the element size */
+#define TP_ERR_TUNING (-5)    /* unknown tuning key or value out of range */
+
+/*
+ * Algorithm 3 (Section 4), fp32 in and out.  Pass 1 evaluates every e^x as a pair
+ * (m, n) with e^x = m * 2^n (ExtExp: Algorithm 4 of Section 6.3 without its
+ * reconstruction step) and reduces the pairs of a row to one (m_sum, n_sum),
+ * always rescaling to the larger exponent so nothing overflows; pass 2 recomputes
+ * each pair and writes y = m * (1 / m_sum) * 2^(n - n_sum).  Reads x twice, writes
+ * y once: 3 N elements of traffic (Table 2).
+ * Beyond |x| = 1e5 the fp32 range reduction loses accuracy (the product
+ * x * log2(e) is rounded to 24 bits); outputs stay finite up to |x| ~ 1e15.
+ */
+TP_API int softmax2p_f32(const float *x, float *y, int64_t rows, int64_t n, void *stream);
+
+/*
+ * Algorithm 1 (Section 3): mu = max x; sigma = sum Exp(x - mu); y = Exp(x - mu) / sigma,
+ * with Exp recomputed in the last pass.  3 reads + 1 write per element (Table 2).
+ */
+TP_API int softmax3p_recompute_f32(const float *x, float *y, int64_t rows, int64_t n, void *stream);
+
+/*
+ * Algorithm 2 (Section 3): as Algorithm 1, but the second pass stores Exp(x - mu) in y
+ * and the third rescales y in place.  3 reads + 2 writes per element (Table 2).
+ */
+TP_API int softmax3p_reload_f32(const float *x, float *y, int64_t rows, int64_t n, void *stream);
+
+/*
+ * Algorithm 3 with bfloat16 storage: x and y hold bf16 bit patterns; each element
+ * is widened to fp32, the pair arithmetic is the fp32 one of softmax2p_f32, and
+ * y is rounded to bf16 (nearest even).  Not in the paper, which is fp32 only
+ * (Section 6.3); target accuracy 1e-2 relative against the unrounded result.
+ */
+TP_API int softmax2p_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n, void *stream);
+
+/* ----- pieces of the path, exported for tests and for per-pass timing ----- */
+
+/*
+ * ExtExp alone (Section 4): m[i], e[i] = pair of x[i] for i < count, e an
+ * integer-valued float.  x, m, e are device pointers to `count` floats.
+ */
+TP_API int softmax_tp_extexp_f32(const float *x, float *m, float *e, int64_t count, void *stream);
+
+/*
+ * Pass 1 of Algorithm 3 including every merge level: pairs[2 r] = m_sum and
+ * pairs[2 r + 1] = n_sum of row r.  pairs is a device pointer to 2 * rows floats.
+ */
+TP_API int softmax2p_f32_pass1(const float *x, float *pairs, int64_t rows, int64_t n, void *stream);
+
+/*
+ * Pass 2 of Algorithm 3 given the per-row pairs produced by softmax2p_f32_pass1.
+ */
+TP_API int softmax2p_f32_pass2(const float *x, const float *pairs, float *y, int64_t rows, int64_t n,
+                        void *stream);
+
+/*
+ * Bandwidth calibration in the manner of the STREAM comparison of Section 6.4,
+ * using the same streaming code as the softmax passes: read `count` floats
+ * (their sum goes to sink[0], a device float), copy y = x, scale y = a * x.
+ */
+TP_API int softmax_tp_stream_read_f32(const float *x, float *sink, int64_t count, void *stream);
+TP_API int softmax_tp_stream_copy_f32(const float *x, float *y, int64_t count, void *stream);
+TP_API int softmax_tp_stream_scale_f32(const float *x, float *y, float a, int64_t count, void *stream);
+
+/* ----- planning, workspace, tuning (host side) ----- */
+
+typedef struct {
+    int32_t path;           /* 1: one workgroup per row, single launch; 2: rows cut into chunks */
+    int32_t block;          /* threads per workgroup */
+    int32_t unroll;         /* 16-byte loads in flight per thread */
+    int32_t vector_elems;   /* elements per access: 4 (fp32) / 8 (bf16), or 1 when unaligned */
+    int32_t merge_kernel;   /* path 2: 1 if partial results are merged by a kernel of their own,
+                               0 if each workgroup of the next pass merges them itself */
+    int32_t launches;       /* kernel launches of the Two-Pass call */
+    int64_t chunk_vecs;     /* path 2: 16-byte vectors per chunk */
+    int64_t chunks;         /* path 2: chunks per row */
+    int64_t workspace_bytes;
+} softmax_tp_plan_t;
+
+/*
+ * The launch plan the library would use.  elem_bytes is 4 or 2; congruent16 says
+ * whether x and y are congruent modulo 16 bytes.  Pure host logic: no GPU needed.
+ */
+TP_API int softmax_tp_plan(int64_t rows, int64_t n, int32_t elem_bytes, int32_t congruent16,
+                    softmax_tp_plan_t *plan);
+
+/*
+ * Overrides a planner parameter (for sweeps): "path" (0 auto, 1, 2), "block_rows",
+ * "unroll_rows", "block_chunk", "unroll_chunk", "target_chunks" (workgroups aimed
+ * for on path 2), "min_chunk_vecs", "fold_max" (largest chunk count merged inside
+ * the next pass).  value 0 restores the default.  Not thread safe against running calls.
+ */
+TP_API int softmax_tp_tune(const char *key, int64_t value);
+
+/* Frees every workspace the library holds (synchronises the device). */
+TP_API int softmax_tp_release(void);
+
+/* Text for a return code of this library (negative codes; positive ones are HIP's). */
+TP_API const char *softmax_tp_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

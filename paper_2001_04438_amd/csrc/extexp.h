@@ -1,0 +1,34 @@
+// ExtExp: e^x as a (mantissa, exponent) pair, and Exp with reconstruction.
+//
+// Section 4 keeps e^x = m * 2^n as the pair (m, n) by dropping the reconstruction
+// step of Algorithm 4 (Section 6.3): n = round(x log2 e), t = x - n ln 2 by a
+// two-constant Cody-Waite reduction, m = 1 + t (c1 + t (c2 + t (c3 + t (c4 + t c5))))
+// in Horner form with fused multiply-adds.  n is an integer held in a float.
+// Both softmax families use this same reduction and polynomial (Section 6.3, last
+// paragraph).
+//
+// The functions are plain scalar code: hipcc compiles them for gfx950
+// (v_rndne_f32, v_fma_f32); a host C compiler can include the file as well so the
+// arithmetic can be swept exhaustively against libm without a GPU.
+#pragma once
+#include "expconst.h"
+
+#if defined(__HIPCC__)
+#define TP_FN __host__ __device__ __forceinline__
+#else
+#define TP_FN static inline
+#endif
+
+TP_FN void tp_extexp(float x, float *m, float *n)
+{
+    float nn = __builtin_rintf(x * TP_LOG2E);        // round to nearest, ties to even
+    float t = __builtin_fmaf(nn, -TP_LN2_HI, x);     // product exact inside the FMA
+    t = __builtin_fmaf(nn, -TP_LN2_LO, t);
+    float p = __builtin_fmaf(TP_EXP_C5, t, TP_EXP_C4);
+    p = __builtin_fmaf(p, t, TP_EXP_C3);
+    p = __builtin_fmaf(p, t, TP_EXP_C2);
+    p = __builtin_fmaf(p, t, TP_EXP_C1);
+    p = __builtin_fmaf(p, t, 1.0f);
+    *m = p;
+    *n = nn;
+}

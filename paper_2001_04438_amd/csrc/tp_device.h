@@ -1,0 +1,559 @@
+// Device-side building blocks of the softmax kernels (gfx950, wave64).
+//
+//  * pair arithmetic for the (m, n) representation of Section 4,
+//  * wave / workgroup reductions (DPP inside a row of 16 lanes, v_readlane across
+//    the four rows, LDS across waves),
+//  * 128-bit coalesced streaming of a row segment with scalar handling of the few
+//    elements before / after the 16-byte-aligned body of a row.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "extexp.h"
+
+namespace tp {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kWave = 64;
+constexpr int kMaxWaves = 16;
+
+// Exponent of the additive identity pair (0, -inf) of Algorithm 3.  A finite
+// stand-in is used so that two identities can meet in a tree reduction without
+// producing (-inf) - (-inf) = NaN; it is below every exponent the evaluator can
+// return for a finite input, and its mantissa is 0 so it never contributes.
+constexpr float kNIdent = -3.402823466e38f;
+
+// float -> int32 with saturation (v_cvt_i32_f32 saturates and maps NaN to 0; a C
+// cast would be undefined for the huge negative differences that occur when an
+// identity pair is rescaled).
+__device__ __forceinline__ int cvt_i32_sat(float f)
+{
+    int r;
+    asm("v_cvt_i32_f32 %0, %1" : "=v"(r) : "v"(f));
+    return r;
+}
+
+// m * 2^dn for an integer-valued float dn <= 0 (Algorithm 3: values are only
+// ever scaled down).  v_ldexp_f32 returns 0 once the result underflows.
+__device__ __forceinline__ float scale_pow2(float m, float dn)
+{
+    return __builtin_ldexpf(m, cvt_i32_sat(dn));
+}
+
+// Exp of Algorithm 4 for a non-positive argument: ExtExp followed by the
+// reconstruction p * 2^n (the v_ldexp_f32 analogue of the VSCALEFPS step).
+__device__ __forceinline__ float exp_nonpos(float d)
+{
+    float m, n;
+    tp_extexp(d, &m, &n);
+    return scale_pow2(m, n);
+}
+
+// ---------------------------------------------------------------------------
+// wave-level reductions
+// ---------------------------------------------------------------------------
+
+template <int CTRL>
+__device__ __forceinline__ float dpp(float v)
+{
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+
+__device__ __forceinline__ float lane_value(float v, int lane)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+
+// DPP controls: quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror.
+// After the four steps every lane of a 16-lane row holds the row's result.
+#define TP_ROW_BUTTERFLY(v, OP)      \
+    v = OP(v, dpp<0xB1>(v));         \
+    v = OP(v, dpp<0x4E>(v));         \
+    v = OP(v, dpp<0x141>(v));        \
+    v = OP(v, dpp<0x140>(v));
+
+__device__ __forceinline__ float op_max(float a, float b) { return fmaxf(a, b); }
+__device__ __forceinline__ float op_add(float a, float b) { return a + b; }
+
+__device__ __forceinline__ float wave_max(float v)
+{
+    TP_ROW_BUTTERFLY(v, op_max)
+    return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)),
+                 fmaxf(lane_value(v, 32), lane_value(v, 48)));
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+    TP_ROW_BUTTERFLY(v, op_add)
+    return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
+}
+
+// 64 pairs -> one: wave maximum of the exponents, each lane rescales its mantissa
+// to it, wave sum of the mantissas.  Same result as 63 pairwise additions.
+__device__ __forceinline__ void wave_pair(float &m, float &n)
+{
+    float nw = wave_max(n);
+    m = wave_sum(scale_pow2(m, n - nw));
+    n = nw;
+}
+
+// ---------------------------------------------------------------------------
+// workgroup-level reductions (result returned to every thread)
+// ---------------------------------------------------------------------------
+
+template <int BLOCK>
+__device__ __forceinline__ float block_max(float v, float *lds)
+{
+    constexpr int W = BLOCK / kWave;
+    v = wave_max(v);
+    if constexpr (W == 1)
+        return v;
+    __syncthreads();  // lds may still be read by an earlier reduction
+    if ((threadIdx.x & (kWave - 1)) == 0)
+        lds[threadIdx.x / kWave] = v;
+    __syncthreads();
+    float r = lds[0];
+#pragma unroll
+    for (int w = 1; w < W; ++w)
+        r = fmaxf(r, lds[w]);
+    return r;
+}
+
+template <int BLOCK>
+__device__ __forceinline__ float block_sum(float v, float *lds)
+{
+    constexpr int W = BLOCK / kWave;
+    v = wave_sum(v);
+    if constexpr (W == 1)
+        return v;
+    __syncthreads();
+    if ((threadIdx.x & (kWave - 1)) == 0)
+        lds[threadIdx.x / kWave] = v;
+    __syncthreads();
+    float r = lds[0];
+#pragma unroll
+    for (int w = 1; w < W; ++w)
+        r += lds[w];
+    return r;
+}
+
+template <int BLOCK>
+__device__ __forceinline__ void block_pair(float &m, float &n, float *lds)
+{
+    constexpr int W = BLOCK / kWave;
+    wave_pair(m, n);
+    if constexpr (W == 1)
+        return;
+    __syncthreads();
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+        lds[threadIdx.x / kWave] = m;
+        lds[kMaxWaves + threadIdx.x / kWave] = n;
+    }
+    __syncthreads();
+    float nb = lds[kMaxWaves];
+#pragma unroll
+    for (int w = 1; w < W; ++w)
+        nb = fmaxf(nb, lds[kMaxWaves + w]);
+    float mb = scale_pow2(lds[0], lds[kMaxWaves] - nb);
+#pragma unroll
+    for (int w = 1; w < W; ++w)
+        mb += scale_pow2(lds[w], lds[kMaxWaves + w] - nb);
+    m = mb;
+    n = nb;
+}
+
+// ---------------------------------------------------------------------------
+// element formats: how 16 bytes (or one element) become floats and back
+// ---------------------------------------------------------------------------
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w)
+{
+    return __builtin_bit_cast(float, w & 0xFFFF0000u);
+}
+__device__ __forceinline__ uint32_t bf16_pack(float lo, float hi)  // round to nearest even
+{
+    f32x2 p = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));
+}
+
+struct F32x4 {  // fp32, 16-byte vectors
+    using elem = float;
+    using vec = f32x4;
+    static constexpr int V = 4;
+    static __device__ __forceinline__ void unpack(vec v, float *o)
+    {
+        o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+    }
+    static __device__ __forceinline__ vec pack(const float *o)
+    {
+        vec v = {o[0], o[1], o[2], o[3]};
+        return v;
+    }
+    static __device__ __forceinline__ float load1(const elem *p) { return *p; }
+    static __device__ __forceinline__ void store1(elem *p, float v) { *p = v; }
+    static __device__ __forceinline__ vec zero() { vec v = {0.f, 0.f, 0.f, 0.f}; return v; }
+};
+
+struct F32x1 {  // fp32, element-wise (x and y not congruent modulo 16 bytes)
+    using elem = float;
+    using vec = float;
+    static constexpr int V = 1;
+    static __device__ __forceinline__ void unpack(vec v, float *o) { o[0] = v; }
+    static __device__ __forceinline__ vec pack(const float *o) { return o[0]; }
+    static __device__ __forceinline__ float load1(const elem *p) { return *p; }
+    static __device__ __forceinline__ void store1(elem *p, float v) { *p = v; }
+    static __device__ __forceinline__ vec zero() { return 0.f; }
+};
+
+struct BF16x8 {  // bf16 in and out, 16-byte vectors, fp32 arithmetic
+    using elem = uint16_t;
+    using vec = u32x4;
+    static constexpr int V = 8;
+    static __device__ __forceinline__ void unpack(vec v, float *o)
+    {
+        o[0] = bf16_lo(v.x); o[1] = bf16_hi(v.x); o[2] = bf16_lo(v.y); o[3] = bf16_hi(v.y);
+        o[4] = bf16_lo(v.z); o[5] = bf16_hi(v.z); o[6] = bf16_lo(v.w); o[7] = bf16_hi(v.w);
+    }
+    static __device__ __forceinline__ vec pack(const float *o)
+    {
+        vec v = {bf16_pack(o[0], o[1]), bf16_pack(o[2], o[3]), bf16_pack(o[4], o[5]),
+                 bf16_pack(o[6], o[7])};
+        return v;
+    }
+    static __device__ __forceinline__ float load1(const elem *p)
+    {
+        return __builtin_bit_cast(float, (uint32_t)(*p) << 16);
+    }
+    static __device__ __forceinline__ void store1(elem *p, float v)
+    {
+        *p = (uint16_t)(bf16_pack(v, 0.f) & 0xFFFFu);
+    }
+    static __device__ __forceinline__ vec zero() { vec v = {0u, 0u, 0u, 0u}; return v; }
+};
+
+struct BF16x1 {  // bf16, element-wise
+    using elem = uint16_t;
+    using vec = uint16_t;
+    static constexpr int V = 1;
+    static __device__ __forceinline__ void unpack(vec v, float *o)
+    {
+        o[0] = __builtin_bit_cast(float, (uint32_t)v << 16);
+    }
+    static __device__ __forceinline__ vec pack(const float *o)
+    {
+        return (uint16_t)(bf16_pack(o[0], 0.f) & 0xFFFFu);
+    }
+    static __device__ __forceinline__ float load1(const elem *p) { return BF16x8::load1(p); }
+    static __device__ __forceinline__ void store1(elem *p, float v) { BF16x8::store1(p, v); }
+    static __device__ __forceinline__ vec zero() { return 0; }
+};
+
+// ---------------------------------------------------------------------------
+// the part of one row that one workgroup streams
+// ---------------------------------------------------------------------------
+//
+// A row starts `a` elements past a 16-byte boundary.  Vector j of the row's frame
+// holds row elements [j V - a, j V - a + V); vectors jlo..jhi-1 lie wholly inside
+// the row and are moved with 128-bit accesses.  The at most V-1 elements before
+// and V-1 after them (or the whole row when it holds no full vector) are "edge"
+// elements handled one per lane.  x and y must be congruent modulo 16 bytes for
+// the vector formats; the host picks the element-wise formats otherwise.
+
+template <class IO>
+struct Seg {
+    const typename IO::vec *xv;  // frame vector 0 of the row in x (16-byte aligned)
+    typename IO::vec *yv;        // the same for y
+    const typename IO::elem *xrow;
+    typename IO::elem *yrow;
+    int64_t vb;     // first frame vector of this workgroup
+    uint32_t cnt;   // number of vectors of this workgroup (< 2^31 / 16)
+    int head;       // edge elements [0, head) ...
+    int64_t tail0;  // ... and [tail0, n), if `edges`
+    int64_t n;
+    bool edges;
+};
+
+template <class IO>
+__device__ __forceinline__ Seg<IO> make_seg(const typename IO::elem *x, typename IO::elem *y,
+                                            int64_t n, int64_t row, int64_t chunk,
+                                            int64_t chunk_vecs)
+{
+    using elem = typename IO::elem;
+    constexpr int V = IO::V;
+    Seg<IO> s;
+    s.xrow = x + row * n;
+    s.yrow = y ? y + row * n : nullptr;
+    s.n = n;
+    const int a = (int)(((uintptr_t)s.xrow / sizeof(elem)) % V);
+    const int64_t jlo = a ? 1 : 0;
+    int64_t jhi = (a + n) / V;
+    if (jhi < jlo)
+        jhi = jlo;
+    s.head = a ? (int)(n < (int64_t)(V - a) ? n : (int64_t)(V - a)) : 0;
+    s.tail0 = jhi > jlo ? jhi * V - a : (int64_t)s.head;
+    s.xv = (const typename IO::vec *)((uintptr_t)s.xrow - (uintptr_t)a * sizeof(elem));
+    s.yv = (typename IO::vec *)((uintptr_t)s.yrow - (uintptr_t)a * sizeof(elem));
+    int64_t vb = jlo + chunk * chunk_vecs;
+    int64_t ve = vb + chunk_vecs;
+    if (vb > jhi) vb = jhi;
+    if (ve > jhi) ve = jhi;
+    s.vb = vb;
+    s.cnt = (uint32_t)(ve - vb);
+    s.edges = chunk == 0;
+    return s;
+}
+
+template <bool NT, class VEC>
+__device__ __forceinline__ VEC ld(const VEC *p)
+{
+    if constexpr (NT)
+        return __builtin_nontemporal_load(p);
+    else
+        return *p;
+}
+
+template <bool NT, class VEC>
+__device__ __forceinline__ void st(VEC *p, VEC v)
+{
+    if constexpr (NT)
+        __builtin_nontemporal_store(v, p);
+    else
+        *p = v;
+}
+
+// Streams a segment through policy P.  Each thread keeps U independent 16-byte
+// loads in flight; consecutive lanes touch consecutive vectors, so one wave
+// instruction moves 1 KiB contiguously.  P provides
+//     static constexpr bool kWrite;
+//     template <int G, int V, bool MASKED> void group(const float *f, float *o, const bool *ok);
+// where f/o hold G = U*V elements and ok[u] says whether vector u is real.
+template <class IO, int BLOCK, int U, bool NT_LOAD, bool NT_STORE, class P>
+__device__ __forceinline__ void stream(const Seg<IO> &s, P &p)
+{
+    using vec = typename IO::vec;
+    constexpr int V = IO::V;
+    constexpr int G = U * V;
+    const vec *xb = s.xv + s.vb;
+    vec *yb = s.yv + s.vb;
+    const uint32_t cnt = s.cnt;
+    uint32_t k = threadIdx.x;
+
+    for (; k + (uint32_t)((U - 1) * BLOCK) < cnt; k += (uint32_t)(U * BLOCK)) {
+        vec v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            v[u] = ld<NT_LOAD>(xb + (k + (uint32_t)(u * BLOCK)));
+        float f[G], o[G];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            IO::unpack(v[u], f + u * V);
+        p.template group<G, V, false>(f, o, nullptr);
+        if constexpr (P::kWrite) {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                st<NT_STORE>(yb + (k + (uint32_t)(u * BLOCK)), IO::pack(o + u * V));
+        }
+    }
+    if (k < cnt) {  // last, partly filled round of this thread
+        vec v[U];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            ok[u] = k + (uint32_t)(u * BLOCK) < cnt;
+            v[u] = ok[u] ? ld<NT_LOAD>(xb + (k + (uint32_t)(u * BLOCK))) : IO::zero();
+        }
+        float f[G], o[G];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            IO::unpack(v[u], f + u * V);
+        p.template group<G, V, true>(f, o, ok);
+        if constexpr (P::kWrite) {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (ok[u])
+                    st<NT_STORE>(yb + (k + (uint32_t)(u * BLOCK)), IO::pack(o + u * V));
+        }
+    }
+    if (s.edges) {
+        const int64_t ntail = s.n - s.tail0;
+        const int64_t nedge = s.head + ntail;
+        if ((int64_t)threadIdx.x < nedge) {
+            const int64_t i = (int)threadIdx.x < s.head ? (int64_t)threadIdx.x
+                                                        : s.tail0 + ((int64_t)threadIdx.x - s.head);
+            float f = IO::load1(s.xrow + i), o;
+            p.template group<1, 1, false>(&f, &o, nullptr);
+            if constexpr (P::kWrite)
+                IO::store1(s.yrow + i, o);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// policies: what happens to each element in a pass
+// ---------------------------------------------------------------------------
+
+template <int G>
+__device__ __forceinline__ float tree_sum(float *v)
+{
+#pragma unroll
+    for (int w = 1; w < G; w *= 2)
+#pragma unroll
+        for (int i = 0; i + w < G; i += 2 * w)
+            v[i] += v[i + w];
+    return v[0];
+}
+
+// Two-Pass, pass 1 (Algorithm 3): accumulate ExtExp pairs.  A whole group is
+// brought to the largest exponent among the group and the running sum, then added.
+struct PairSum {
+    static constexpr bool kWrite = false;
+    float m = 0.f, n = kNIdent;
+    template <int G, int V, bool MASKED>
+    __device__ __forceinline__ void group(const float *f, float *, const bool *ok)
+    {
+        float mi[G], ni[G];
+        float nmax = n;
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            tp_extexp(f[i], &mi[i], &ni[i]);
+            if (MASKED && !ok[i / V]) {
+                mi[i] = 0.f;
+                ni[i] = kNIdent;
+            }
+            nmax = fmaxf(nmax, ni[i]);
+        }
+        float acc = scale_pow2(m, n - nmax);
+#pragma unroll
+        for (int i = 0; i < G; ++i)
+            mi[i] = scale_pow2(mi[i], ni[i] - nmax);
+        m = acc + tree_sum<G>(mi);
+        n = nmax;
+    }
+};
+
+// Two-Pass, pass 2: Y_i = m_i * lambda * 2^(n_i - n_sum).
+struct PairOut {
+    static constexpr bool kWrite = true;
+    float lambda, n_sum;
+    template <int G, int V, bool MASKED>
+    __device__ __forceinline__ void group(const float *f, float *o, const bool *)
+    {
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            float mi, ni;
+            tp_extexp(f[i], &mi, &ni);
+            o[i] = scale_pow2(mi * lambda, ni - n_sum);
+        }
+    }
+};
+
+// Three-Pass, pass 1: running maximum.
+struct MaxOf {
+    static constexpr bool kWrite = false;
+    float mx = -__builtin_inff();
+    template <int G, int V, bool MASKED>
+    __device__ __forceinline__ void group(const float *f, float *, const bool *ok)
+    {
+#pragma unroll
+        for (int i = 0; i < G; ++i)
+            if (!MASKED || ok[i / V])
+                mx = fmaxf(mx, f[i]);
+    }
+};
+
+// Three-Pass (recompute), pass 2: sigma += Exp(x - mu).
+struct SumExp {
+    static constexpr bool kWrite = false;
+    float mu;
+    float s = 0.f;
+    template <int G, int V, bool MASKED>
+    __device__ __forceinline__ void group(const float *f, float *, const bool *ok)
+    {
+        float e[G];
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            e[i] = exp_nonpos(f[i] - mu);
+            if (MASKED && !ok[i / V])
+                e[i] = 0.f;
+        }
+        s += tree_sum<G>(e);
+    }
+};
+
+// Three-Pass (recompute), pass 3: Y_i = lambda * Exp(x - mu).
+struct ExpScale {
+    static constexpr bool kWrite = true;
+    float mu, lambda;
+    template <int G, int V, bool MASKED>
+    __device__ __forceinline__ void group(const float *f, float *o, const bool *)
+    {
+#pragma unroll
+        for (int i = 0; i < G; ++i)
+            o[i] = lambda * exp_nonpos(f[i] - mu);
+    }
+};
+
+// Three-Pass (reload), pass 2: Y_i = Exp(x - mu), sigma += Y_i.
+struct ExpStoreSum {
+    static constexpr bool kWrite = true;
+    float mu;
+    float s = 0.f;
+    template <int G, int V, bool MASKED>
+    __device__ __forceinline__ void group(const float *f, float *o, const bool *ok)
+    {
+        float e[G];
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            o[i] = exp_nonpos(f[i] - mu);
+            e[i] = (MASKED && !ok[i / V]) ? 0.f : o[i];
+        }
+        s += tree_sum<G>(e);
+    }
+};
+
+// Three-Pass (reload), pass 3 and the STREAM-Scale calibration: Y_i = lambda * Y_i.
+struct Scale {
+    static constexpr bool kWrite = true;
+    float lambda;
+    template <int G, int V, bool MASKED>
+    __device__ __forceinline__ void group(const float *f, float *o, const bool *)
+    {
+#pragma unroll
+        for (int i = 0; i < G; ++i)
+            o[i] = lambda * f[i];
+    }
+};
+
+// Calibration: plain sum (read-only stream) and copy.
+struct SumOf {
+    static constexpr bool kWrite = false;
+    float s = 0.f;
+    template <int G, int V, bool MASKED>
+    __device__ __forceinline__ void group(const float *f, float *, const bool *ok)
+    {
+        float e[G];
+#pragma unroll
+        for (int i = 0; i < G; ++i)
+            e[i] = (MASKED && !ok[i / V]) ? 0.f : f[i];
+        s += tree_sum<G>(e);
+    }
+};
+
+struct Copy {
+    static constexpr bool kWrite = true;
+    template <int G, int V, bool MASKED>
+    __device__ __forceinline__ void group(const float *f, float *o, const bool *)
+    {
+#pragma unroll
+        for (int i = 0; i < G; ++i)
+            o[i] = f[i];
+    }
+};
+
+}  // namespace tp

@@ -1,0 +1,365 @@
+"""GPU parity: every C-ABI softmax entry point against the long-double oracle.
+
+All tests call through the ctypes binding of libsoftmax_tp.so (no fallback) and
+compare element by element with the oracle's streaming comparator:
+
+  fp32 I/O, Two-Pass     |y - p| <= 4e-6 p      where p >= FLT_MIN
+  bf16 I/O, Two-Pass     |y - p| <= 1e-2 p      (p is the unrounded long-double value)
+  fp32 I/O, Three-Pass   |y - p| <= 1e-5 p      (the fp32 subtraction x - mu alone costs up to
+                                                 2^-24 |x - mu| <= 5.2e-6 while p >= FLT_MIN)
+  p < FLT_MIN            |y - p| <= FLT_MIN     (flushed zero or denormal both pass)
+  every y finite, >= 0;  |sum_i y_i - 1| <= tol + n 2^-126
+"""
+import math
+
+import numpy as np
+import pytest
+
+from paper_2001_04438_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+TOL_2P = 4e-6
+TOL_3P = 1e-5
+TOL_BF16 = 1e-2
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2001_04438_amd import binding
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    binding.lib()  # raises if the HIP library has not been built
+    yield binding
+    for key in ("path", "block_rows", "unroll_rows", "block_chunk", "unroll_chunk",
+                "target_chunks", "min_chunk_vecs", "fold_max"):
+        binding.softmax_tp_tune(key, 0)
+    binding.softmax_tp_release()
+
+
+def _run(fn, x, inplace=False, x_off=0, y_off=0):
+    """Runs a softmax entry point on a numpy array (fp32, or uint16 holding bf16 bits).
+
+    x_off / y_off shift the device buffers by that many elements to exercise
+    unaligned base pointers."""
+    import torch
+    rows, n = x.shape
+    flat = np.ascontiguousarray(x).reshape(-1)
+    host = torch.from_numpy(flat.view(np.int16) if flat.dtype == np.uint16 else flat)
+    xbuf = torch.empty(flat.size + 16, dtype=host.dtype, device="cuda")
+    xd = xbuf[x_off:x_off + flat.size]
+    xd.copy_(host)
+    if inplace:
+        yd = xd
+    else:
+        ybuf = torch.full((flat.size + 16,), -7, dtype=host.dtype, device="cuda")
+        yd = ybuf[y_off:y_off + flat.size]
+    fn(xd, yd, rows, n)
+    torch.cuda.synchronize()
+    if not inplace:
+        # nothing outside the output range may be touched
+        assert (ybuf[:y_off] == -7).all() and (ybuf[y_off + flat.size:] == -7).all()
+    y = yd.cpu().numpy()
+    if flat.dtype == np.uint16:
+        y = y.view(np.uint16)
+    return y.reshape(rows, n)
+
+
+def _check(oracle_mod, x, y, tol, bf16=False):
+    c = oracle_mod.compare(x, y, tol, bf16=bf16)
+    n = x.shape[1]
+    assert c.n_total == x.size
+    assert c.ok(), c.as_dict()
+    assert c.max_row_sum_dev <= (tol if not bf16 else 2 * tol) + n * 2.0 ** -126, c.as_dict()
+    return c
+
+
+ALGOS_F32 = [("softmax2p_f32", TOL_2P), ("softmax3p_recompute_f32", TOL_3P),
+             ("softmax3p_reload_f32", TOL_3P)]
+
+
+# ---------------------------------------------------------------------------
+# the benchmark configurations (small one in full, large ones at reduced row
+# counts here and at full size in test_gpu_full_configs.py)
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name,tol", ALGOS_F32)
+@pytest.mark.parametrize("probes", [False, True])
+def test_cfg1_single_vector(gpu, oracle_mod, name, tol, probes):
+    x = workloads.cfg1(probes=probes)
+    y = _run(getattr(gpu, name), x)
+    _check(oracle_mod, x, y, tol)
+    if probes:  # e^(1e4) overflows any fp32 exp; the result must be the one-hot limit
+        assert y[0, 0] == 1.0 and y[0, 1] == 0.0 and y[0, 2:].max() == 0.0
+
+
+@pytest.mark.parametrize("name,tol", ALGOS_F32)
+def test_cfg2_rows_path(gpu, oracle_mod, name, tol):
+    x = workloads.cfg2(rows=37, n=32768)
+    assert gpu.softmax_tp_plan(37, 32768).path == 1
+    _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
+
+
+@pytest.mark.parametrize("name,tol", ALGOS_F32)
+def test_cfg3_chunk_path(gpu, oracle_mod, name, tol):
+    x = workloads.cfg3(rows=3, n=1_000_000)
+    plan = gpu.softmax_tp_plan(3, 1_000_000)
+    assert plan.path == 2 and plan.chunks > 1
+    _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
+
+
+@pytest.mark.parametrize("name,tol", ALGOS_F32)
+def test_cfg4_single_long_vector(gpu, oracle_mod, name, tol):
+    n = (1 << 23) + 3  # several hundred chunks, merge kernel, ragged tail
+    x = workloads.cfg4(n=n)
+    plan = gpu.softmax_tp_plan(1, n)
+    assert plan.path == 2 and plan.merge_kernel == 1
+    c = _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
+    assert c.n_normal < x.size // 100  # almost everything underflows next to the outliers
+
+
+def test_cfg5_bf16(gpu, oracle_mod):
+    x = workloads.cfg5(rows=61, n=21846)  # row pitch 43692 B: rows start 0/12/8/4 bytes past 16
+    y = _run(gpu.softmax2p_bf16io, x)
+    _check(oracle_mod, x, y, TOL_BF16, bf16=True)
+
+
+def test_bf16_chunk_path(gpu, oracle_mod):
+    x = workloads.cfg5(rows=2, n=300_001)
+    assert gpu.softmax_tp_plan(2, 300_001, 2).path == 2
+    _check(oracle_mod, x, _run(gpu.softmax2p_bf16io, x), TOL_BF16, bf16=True)
+
+
+# ---------------------------------------------------------------------------
+# edge shapes, alignment, aliasing
+# ---------------------------------------------------------------------------
+
+EDGE_N = [1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 63, 64, 65, 255, 256, 257, 1023, 1024, 1025, 4095,
+          4099, 16385]
+
+
+@pytest.mark.parametrize("name,tol", ALGOS_F32)
+def test_edge_lengths_f32(gpu, oracle_mod, name, tol):
+    rng = np.random.default_rng(77)
+    for n in EDGE_N:
+        for rows in (1, 3):
+            x = rng.normal(0, 6, size=(rows, n)).astype(np.float32)
+            y = _run(getattr(gpu, name), x)
+            _check(oracle_mod, x, y, tol)
+            if n == 1:
+                assert np.all(y == 1.0)
+
+
+def test_edge_lengths_bf16(gpu, oracle_mod):
+    rng = np.random.default_rng(78)
+    for n in EDGE_N:
+        for rows in (1, 5):
+            x = workloads.f32_to_bf16_bits(rng.normal(0, 6, size=(rows, n)).astype(np.float32))
+            x = x.reshape(rows, n)
+            _check(oracle_mod, x, _run(gpu.softmax2p_bf16io, x), TOL_BF16, bf16=True)
+
+
+@pytest.mark.parametrize("name,tol", ALGOS_F32)
+def test_unaligned_and_incongruent_pointers_f32(gpu, oracle_mod, name, tol):
+    rng = np.random.default_rng(79)
+    x = rng.normal(0, 5, size=(4, 1001)).astype(np.float32)
+    for x_off, y_off in ((1, 1), (3, 3), (2, 2), (0, 1), (3, 0), (1, 2)):
+        _check(oracle_mod, x, _run(getattr(gpu, name), x, x_off=x_off, y_off=y_off), tol)
+    big = workloads.cfg3(rows=2, n=200_003)  # chunk path, rows not 16-byte aligned
+    for x_off, y_off in ((0, 0), (1, 1), (1, 3)):
+        _check(oracle_mod, big, _run(getattr(gpu, name), big, x_off=x_off, y_off=y_off), tol)
+
+
+def test_unaligned_and_incongruent_pointers_bf16(gpu, oracle_mod):
+    x = workloads.cfg5(rows=5, n=1003)
+    for x_off, y_off in ((0, 0), (1, 1), (7, 7), (0, 1), (5, 2)):
+        y = _run(gpu.softmax2p_bf16io, x, x_off=x_off, y_off=y_off)
+        _check(oracle_mod, x, y, TOL_BF16, bf16=True)
+
+
+@pytest.mark.parametrize("name,tol", ALGOS_F32)
+def test_in_place(gpu, oracle_mod, name, tol):
+    for x in (workloads.cfg2(rows=33, n=5000), workloads.cfg3(rows=2, n=150_001)):
+        _check(oracle_mod, x, _run(getattr(gpu, name), x, inplace=True), tol)
+
+
+def test_in_place_bf16(gpu, oracle_mod):
+    x = workloads.cfg5(rows=9, n=3001)
+    _check(oracle_mod, x, _run(gpu.softmax2p_bf16io, x, inplace=True), TOL_BF16, bf16=True)
+
+
+def test_empty_and_invalid_arguments(gpu):
+    import torch
+    t = torch.zeros(64, dtype=torch.float32, device="cuda")
+    for fn in (gpu.softmax2p_f32, gpu.softmax3p_recompute_f32, gpu.softmax3p_reload_f32):
+        fn(t, t, 0, 5)
+        fn(t, t, 5, 0)
+        fn(None, None, 0, 0)
+        for args, code in (((t, t, -1, 4), gpu.TP_ERR_NEGATIVE), ((None, t, 1, 4), gpu.TP_ERR_NULL),
+                           ((t, None, 1, 4), gpu.TP_ERR_NULL),
+                           ((t, t, 1 << 40, 1 << 40), gpu.TP_ERR_TOO_LARGE),
+                           ((t.data_ptr() + 2, t, 1, 4), gpu.TP_ERR_ALIGN)):
+            with pytest.raises(gpu.SoftmaxTpError) as e:
+                fn(*args)
+            assert e.value.code == code
+    torch.cuda.synchronize()
+    assert float(t.abs().sum()) == 0.0
+
+
+def test_nan_poisons_only_its_row(gpu):
+    x = workloads.cfg2(rows=34, n=3000)
+    x[5, 17] = np.nan
+    for name, _ in ALGOS_F32:
+        y = _run(getattr(gpu, name), x)
+        assert np.isnan(y[5]).all()
+        assert np.isfinite(np.delete(y, 5, axis=0)).all()
+
+
+# ---------------------------------------------------------------------------
+# wide dynamic range: nothing overflows, shift invariance
+# ---------------------------------------------------------------------------
+
+def test_extreme_magnitudes_two_pass(gpu, oracle_mod):
+    rng = np.random.default_rng(80)
+    base = rng.normal(0, 3, size=(6, 2000)).astype(np.float32)
+    for c in (0.0, 88.0, -104.0, 1e4, -1e4, 9e4, -9e4):
+        x = (base + np.float32(c)).astype(np.float32)
+        y = _run(gpu.softmax2p_f32, x)
+        _check(oracle_mod, x, y, TOL_2P)
+    # rows mixing huge positive and negative entries
+    x = base.copy()
+    x[:, ::7] += np.float32(5e3)
+    x[:, 1::7] -= np.float32(7e4)
+    _check(oracle_mod, x, _run(gpu.softmax2p_f32, x), TOL_2P)
+    xb = workloads.f32_to_bf16_bits(x).reshape(x.shape)
+    _check(oracle_mod, xb, _run(gpu.softmax2p_bf16io, xb), TOL_BF16, bf16=True)
+
+
+def test_shift_invariance_on_gpu(gpu):
+    rng = np.random.default_rng(81)
+    x = (rng.integers(-3000, 3000, size=(4, 777)) / 256.0).astype(np.float32)
+    y0 = _run(gpu.softmax2p_f32, x)
+    for c in (64.0, -512.0, 8192.0):
+        yc = _run(gpu.softmax2p_f32, (x + np.float32(c)).astype(np.float32))
+        nz = y0 > 1e-30
+        assert np.max(np.abs(yc[nz] - y0[nz]) / y0[nz]) < 2 * TOL_2P
+
+
+# ---------------------------------------------------------------------------
+# pieces of the path: ExtExp, pass 1 pairs, pass 2
+# ---------------------------------------------------------------------------
+
+def test_extexp_pairs(gpu, oracle_mod):
+    import torch
+    rng = np.random.default_rng(82)
+    xs = np.concatenate([
+        np.linspace(-104, 89, 200_001), rng.uniform(-1e5, 1e5, 100_000),
+        rng.normal(0, 1e-3, 1000), [0.0, -0.0, 1e4, -1e4, 88.72, -103.97, 0.34657359, -0.34657359],
+    ]).astype(np.float32)
+    xd = torch.from_numpy(xs).cuda()
+    md = torch.empty_like(xd)
+    ed = torch.empty_like(xd)
+    gpu.softmax_tp_extexp_f32(xd, md, ed, xs.size)
+    torch.cuda.synchronize()
+    m, e = md.cpu().numpy(), ed.cpu().numpy()
+    assert np.all(e == np.rint(e))                                   # n is an integer
+    assert np.all(np.abs(e - xs.astype(np.float64) * 1.4426950408889634) <= 0.5 + 1e-2)
+    inner = np.abs(xs) <= 1e4
+    # Section 4: m = e^t in [sqrt(2)/2, sqrt(2)] (up to the slop of rounding x log2 e)
+    assert m[inner].min() >= math.sqrt(2) / 2 * (1 - 2e-3) and m[inner].max() <= math.sqrt(2) * (1 + 2e-3)
+    rel, worst = oracle_mod.pair_rel_err(xs, m, e)
+    assert rel[inner].max() < 2.5e-7       # 2 ULP of a value just below a power of two
+    assert worst < 4e-7                    # |x| up to 1e5: reduced argument slightly outside the fit
+
+
+def test_pass1_pairs_and_pass2(gpu, oracle_mod):
+    import torch
+    for x in (workloads.cfg1(probes=True), workloads.cfg3(rows=5, n=70_001), workloads.cfg4(n=3_000_000)):
+        rows, n = x.shape
+        xd = torch.from_numpy(x.reshape(-1)).cuda()
+        pairs = torch.empty(2 * rows, dtype=torch.float32, device="cuda")
+        gpu.softmax2p_f32_pass1(xd, pairs, rows, n)
+        yd = torch.empty_like(xd)
+        gpu.softmax2p_f32_pass2(xd, pairs, yd, rows, n)
+        torch.cuda.synchronize()
+        p = pairs.cpu().numpy().reshape(rows, 2)
+        for r in range(rows):
+            m_sum, n_sum = float(p[r, 0]), float(p[r, 1])
+            assert n_sum == round(n_sum) and m_sum >= 0.7
+            # n_sum is the largest exponent in the row
+            assert abs(n_sum - float(x[r].max()) * 1.4426950408889634) <= 0.51
+            lse = float(oracle_mod.logsumexp(x[r]))
+            assert abs(math.log(m_sum) + n_sum * math.log(2.0) - lse) < 3e-6
+        _check(oracle_mod, x, yd.cpu().numpy().reshape(rows, n), TOL_2P)
+
+
+def test_two_pass_and_three_pass_agree(gpu):
+    x = workloads.cfg2(rows=35, n=8192)
+    y2 = _run(gpu.softmax2p_f32, x)
+    for name in ("softmax3p_recompute_f32", "softmax3p_reload_f32"):
+        y3 = _run(getattr(gpu, name), x)
+        nz = y2 > 1e-30
+        assert np.max(np.abs(y3[nz] - y2[nz]) / y2[nz]) < 1e-5
+
+
+# ---------------------------------------------------------------------------
+# every launch shape gives the same answer; runs are reproducible
+# ---------------------------------------------------------------------------
+
+def test_launch_shapes(gpu, oracle_mod):
+    x = workloads.cfg3(rows=4, n=50_003)
+    xb = workloads.cfg5(rows=4, n=50_003)
+    try:
+        for path in (1, 2):
+            gpu.softmax_tp_tune("path", path)
+            for block in (256, 512, 1024):
+                for unroll in (2, 4, 8):
+                    for key in ("block_rows", "block_chunk"):
+                        gpu.softmax_tp_tune(key, block)
+                    for key in ("unroll_rows", "unroll_chunk"):
+                        gpu.softmax_tp_tune(key, unroll)
+                    for name, tol in ALGOS_F32:
+                        _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
+                    if unroll < 8:
+                        _check(oracle_mod, xb, _run(gpu.softmax2p_bf16io, xb), TOL_BF16, bf16=True)
+                    else:
+                        with pytest.raises(gpu.SoftmaxTpError):
+                            _run(gpu.softmax2p_bf16io, xb)
+        # chunk path with the partials merged by the separate kernel vs inside pass 2
+        gpu.softmax_tp_tune("path", 2)
+        gpu.softmax_tp_tune("block_chunk", 256)
+        gpu.softmax_tp_tune("unroll_chunk", 2)
+        gpu.softmax_tp_tune("min_chunk_vecs", 512)
+        outs = []
+        for fold in (1, 1000):
+            gpu.softmax_tp_tune("fold_max", fold)
+            assert gpu.softmax_tp_plan(4, 50_003).merge_kernel == (1 if fold == 1 else 0)
+            outs.append([_run(getattr(gpu, name), x) for name, _ in ALGOS_F32])
+        for a, b in zip(*outs):
+            assert np.array_equal(a, b)
+    finally:
+        for key in ("path", "block_rows", "unroll_rows", "block_chunk", "unroll_chunk",
+                    "min_chunk_vecs", "fold_max"):
+            gpu.softmax_tp_tune(key, 0)
+
+
+def test_bitwise_reproducible(gpu):
+    x = workloads.cfg3(rows=2, n=400_000)
+    for name, _ in ALGOS_F32:
+        a = _run(getattr(gpu, name), x)
+        b = _run(getattr(gpu, name), x)
+        assert np.array_equal(a, b)
+
+
+def test_calibration_streams(gpu):
+    import torch
+    n = (1 << 22) + 5
+    x = torch.arange(n, dtype=torch.float32, device="cuda") % 7
+    y = torch.empty_like(x)
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    gpu.softmax_tp_stream_copy_f32(x, y, n)
+    assert torch.equal(x, y)
+    gpu.softmax_tp_stream_scale_f32(x, y, 2.5, n)
+    assert torch.equal(x * 2.5, y)
+    gpu.softmax_tp_stream_read_f32(x, sink, n)
+    assert abs(float(sink[0]) - float(x.double().sum())) <= 1e-6 * float(x.double().sum())
