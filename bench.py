@@ -1,0 +1,278 @@
+#!/usr/bin/env python3
+"""Benchmark of the Two-Pass softmax hot path on one MI355X.
+
+A step is one call of softmax2p_f32 (every pass of Algorithm 3) on the headline
+workload, with the input already resident in HBM.  Prints ONE JSON line:
+
+  value / unit     whole-job algorithmic bandwidth of the Two-Pass call in GB/s,
+                   counting 3 N s bytes (Table 2: two reads and one write per element)
+  roofline         the dominant kernel (pass 2: read x, write y = 2 N s bytes) timed
+                   per launch with events on the launch stream, against 8 TB/s HBM
+  cpu_baseline     the long-double oracle on the same input, on the host cores
+  variants         Three-Pass baselines on the same input (4 N s and 5 N s bytes)
+  calibration      read / copy / scale streams at 1 GiB (the STREAM comparison of
+                   Section 6.4)
+  other_workloads  the remaining configurations, each with all variants
+
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4] [--quick]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+BYTES_PER_ELEM = {"softmax2p": 3, "softmax3p_recompute": 4, "softmax3p_reload": 5}  # x element size
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def _events(torch, k):
+    return [torch.cuda.Event(enable_timing=True) for _ in range(k)]
+
+
+def time_calls(torch, fn, steps, warmup, sets):
+    """Wall-clock and event time of `steps` calls of fn(set_index), rotating over buffer sets."""
+    for i in range(warmup):
+        fn(i % sets)
+    torch.cuda.synchronize()
+    e0, e1 = _events(torch, 2)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(steps):
+        fn(i % sets)
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+
+def per_launch_ms(torch, fn, steps, sets):
+    """Average duration of one launch of fn, each launch bracketed by its own pair of events
+    recorded on the stream the kernel runs on (torch's current stream)."""
+    evs = [_events(torch, 2) for _ in range(steps)]
+    torch.cuda.synchronize()
+    for i in range(steps):
+        evs[i][0].record()
+        fn(i % sets)
+        evs[i][1].record()
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) for a, b in evs)
+    return sum(ts) / len(ts), ts[len(ts) // 2], ts[0]
+
+
+def load_traffic(workload, kernel):
+    """HBM bytes per launch measured with rocprofv3 counters, if a summary has been recorded."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload, {}).get(kernel)
+    except (OSError, ValueError):
+        return None
+
+
+def run_workload(torch, B, W, name, steps, warmup, full):
+    import numpy as np
+
+    rows, n = W.SHAPES[name]
+    bf16 = W.DTYPES[name] == "bf16"
+    s = 2 if bf16 else 4
+    t0 = time.perf_counter()
+    x_host = W.make(name)
+    log(f"[bench] {name}: generated {rows}x{n} {W.DTYPES[name]} in {time.perf_counter() - t0:.1f}s")
+    flat = x_host.reshape(-1)
+    host_t = torch.from_numpy(flat.view(np.int16) if bf16 else flat)
+    footprint = 2 * flat.size * s
+    sets = 1 if footprint >= (1 << 30) else int(min(8, -(-(1 << 30) // footprint)))
+    xs = [host_t.cuda() for _ in range(sets)]
+    ys = [torch.empty_like(xs[0]) for _ in range(sets)]
+    elems = rows * n
+    plan = B.softmax_tp_plan(rows, n, s, True)
+    out = {"rows": rows, "n": n, "dtype": "bf16" if bf16 else "f32", "buffer_sets": sets,
+           "plan": plan.as_dict(), "variants": {}}
+
+    variants = [("softmax2p", B.softmax2p_bf16io if bf16 else B.softmax2p_f32)]
+    if not bf16:
+        variants += [("softmax3p_recompute", B.softmax3p_recompute_f32),
+                     ("softmax3p_reload", B.softmax3p_reload_f32)]
+    for vname, fn in variants:
+        call = lambda i, fn=fn: fn(xs[i], ys[i], rows, n)
+        wall_ms, ev_ms = time_calls(torch, call, steps, warmup, sets)
+        alg_bytes = BYTES_PER_ELEM[vname] * elems * s
+        out["variants"][vname] = {
+            "ms_per_step": wall_ms, "ms_per_step_events": ev_ms,
+            "algorithmic_bytes": alg_bytes, "GBps": alg_bytes / wall_ms / 1e6,
+            "elements_per_s": elems / wall_ms * 1e3,
+            "frac_of_hbm_peak": alg_bytes / wall_ms / 1e6 / HBM_PEAK_GBS,
+        }
+        log(f"[bench] {name} {vname}: {wall_ms:.4f} ms/step, {alg_bytes / wall_ms / 1e6:.0f} GB/s")
+
+    # dominant kernel, one launch at a time
+    if plan.path == 2 and not bf16:
+        pairs = torch.empty(2 * rows, dtype=torch.float32, device="cuda")
+        B.softmax2p_f32_pass1(xs[0], pairs, rows, n)
+        p1 = per_launch_ms(torch, lambda i: B.softmax2p_f32_pass1(xs[i], pairs, rows, n), steps, sets)
+        p2 = per_launch_ms(torch, lambda i: B.softmax2p_f32_pass2(xs[i], pairs, ys[i], rows, n),
+                           steps, sets)
+        out["pass1_ms"] = {"avg": p1[0], "median": p1[1], "min": p1[2], "bytes": elems * s}
+        out["pass2_ms"] = {"avg": p2[0], "median": p2[1], "min": p2[2], "bytes": 2 * elems * s}
+        dom_name, dom_ms, dom_bytes = "chunk_2p_pass2", p2[0], 2 * elems * s
+    else:
+        fn = variants[0][1]
+        k = per_launch_ms(torch, lambda i: fn(xs[i], ys[i], rows, n), steps, sets)
+        out["kernel_ms"] = {"avg": k[0], "median": k[1], "min": k[2]}
+        dom_name, dom_ms, dom_bytes = "rows_2p", k[0], 3 * elems * s
+    out["dominant"] = {"kernel": dom_name, "avg_ms": dom_ms, "algorithmic_bytes": dom_bytes,
+                       "GBps": dom_bytes / dom_ms / 1e6,
+                       "traffic_bytes": load_traffic(name, dom_name)}
+    torch.cuda.synchronize()
+    y_host = None
+    if full:
+        variants[0][1](xs[0], ys[0], rows, n)
+        torch.cuda.synchronize()
+        y_host = ys[0].cpu().numpy()
+        if bf16:
+            y_host = y_host.view(np.uint16)
+        y_host = y_host.reshape(rows, n)
+    del xs, ys
+    torch.cuda.empty_cache()
+    return out, x_host, y_host
+
+
+def calibration(torch, B, steps, warmup):
+    n = 1 << 28
+    x = torch.rand(n, dtype=torch.float32, device="cuda")
+    y = torch.empty_like(x)
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    res = {}
+    for name, fn, nbytes in (
+            ("read", lambda i: B.softmax_tp_stream_read_f32(x, sink, n), 4 * n),
+            ("copy", lambda i: B.softmax_tp_stream_copy_f32(x, y, n), 8 * n),
+            ("scale", lambda i: B.softmax_tp_stream_scale_f32(x, y, 0.5, n), 8 * n)):
+        for i in range(warmup):
+            fn(0)
+        avg, med, mn = per_launch_ms(torch, fn, steps, 1)
+        res[name] = {"ms": avg, "GBps": nbytes / avg / 1e6, "frac_of_hbm_peak": nbytes / avg / 1e6 / HBM_PEAK_GBS}
+        log(f"[bench] stream_{name} 1 GiB: {avg:.4f} ms, {nbytes / avg / 1e6:.0f} GB/s")
+    return res
+
+
+def cpu_baseline(x_host, y_host, bf16, tol):
+    """Times the oracle as it stands on the host cores and checks the GPU output with it."""
+    import oracle
+    cores = oracle.threads_available()
+    t0 = time.perf_counter()
+    mu, S = oracle.stats(x_host, bf16=bf16)
+    t_stats = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    cmp_ = oracle.compare(x_host, y_host, tol, bf16=bf16)  # recomputes mu, S, then every p_i
+    t_cmp = time.perf_counter() - t0
+    # softmax = statistics pass + one exp and one division per element: the comparator does
+    # exactly that work (plus the comparison), so its time stands for a full oracle softmax
+    return cores, t_stats, t_cmp, cmp_
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg4", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--quick", action="store_true", help="headline workload only")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import torch
+    from paper_2001_04438_amd import binding as B
+    from paper_2001_04438_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    B.lib()  # fails loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+    props = torch.cuda.get_device_properties(0)
+    log(f"[bench] device: {props.name}, {props.multi_processor_count} CUs")
+
+    head, x_host, y_host = run_workload(torch, B, W, args.workload, args.steps, args.warmup, True)
+    bf16 = head["dtype"] == "bf16"
+    tol = 1e-2 if bf16 else 4e-6
+    cores, t_stats, t_cmp, cmp_ = cpu_baseline(x_host, y_host, bf16, tol)
+    log(f"[bench] oracle on {cores} threads: stats {t_stats:.2f}s, softmax+compare {t_cmp:.2f}s; "
+        f"GPU max_rel_err={cmp_.max_rel_err:.3e} ok={cmp_.ok()}")
+    del x_host, y_host
+
+    two = head["variants"]["softmax2p"]
+    s = 2 if bf16 else 4
+    elems = head["rows"] * head["n"]
+    dom = head["dominant"]
+    result = {
+        "metric": "softmax GB/s and elements/s per MI355X; % of HBM peak; 2-pass vs 3-pass",
+        "value": two["GBps"],
+        "unit": "GB/s (Two-Pass softmax, algorithmic bytes 3*N*s per call)",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": two["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if not bf16 else "f32 (bf16 storage)",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {head['rows']} x {head['n']} {head['dtype']}",
+                   "plan": head["plan"], "buffer_sets": head["buffer_sets"]},
+        "elements_per_s": two["elements_per_s"],
+        "frac_of_hbm_peak": two["frac_of_hbm_peak"],
+        "roofline": {
+            "bound": "hbm", "kernel": dom["kernel"],
+            "achieved": dom["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": dom["GBps"] / HBM_PEAK_GBS,
+            "algorithmic_bytes_per_launch": dom["algorithmic_bytes"],
+            "avg_launch_ms": dom["avg_ms"],
+            "traffic": dom["traffic_bytes"],
+        },
+        "cpu_baseline": {
+            "value": 3 * elems * s / t_cmp / 1e9, "unit": "GB/s (same 3*N*s byte count)",
+            "elements_per_s": elems / t_cmp, "seconds": t_cmp, "cores": cores, "kind": "oracle",
+            "sample": f"the whole {args.workload} input, one oracle softmax fused with the comparison "
+                      f"of the GPU output (statistics pass alone: {t_stats:.2f}s)",
+        },
+        "parity": {"max_rel_err": cmp_.max_rel_err, "tolerance": tol, "ok": bool(cmp_.ok()),
+                   "max_row_sum_dev": cmp_.max_row_sum_dev},
+        "variants": {k: {kk: v[kk] for kk in ("ms_per_step", "GBps", "elements_per_s", "frac_of_hbm_peak")}
+                     for k, v in head["variants"].items()},
+        "passes": {k: head[k] for k in ("pass1_ms", "pass2_ms", "kernel_ms") if k in head},
+    }
+    if "softmax3p_recompute" in head["variants"]:
+        result["two_pass_speedup"] = {
+            "vs_recompute": head["variants"]["softmax3p_recompute"]["ms_per_step"] / two["ms_per_step"],
+            "vs_reload": head["variants"]["softmax3p_reload"]["ms_per_step"] / two["ms_per_step"]}
+    if not args.quick:
+        result["calibration"] = calibration(torch, B, args.steps, args.warmup)
+        others = {}
+        for name in ("cfg2", "cfg3", "cfg4", "cfg5"):
+            if name == args.workload:
+                continue
+            o, _, _ = run_workload(torch, B, W, name, args.steps, args.warmup, False)
+            others[name] = {
+                "shape": f"{o['rows']} x {o['n']} {o['dtype']}", "path": o["plan"]["path"],
+                "buffer_sets": o["buffer_sets"],
+                "variants": {k: {kk: v[kk] for kk in ("ms_per_step", "GBps", "frac_of_hbm_peak")}
+                             for k, v in o["variants"].items()},
+                "dominant": o["dominant"]}
+        result["other_workloads"] = others
+    B.softmax_tp_release()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -146,8 +146,8 @@ def test_edge_lengths_f32(gpu, oracle_mod, name, tol):
             x = rng.normal(0, 6, size=(rows, n)).astype(np.float32)
             y = _run(getattr(gpu, name), x)
             _check(oracle_mod, x, y, tol)
-            if n == 1:
-                assert np.all(y == 1.0)
+            if n == 1:  # m * fl(1 / m) may be one rounding below 1 (Algorithm 3 multiplies by lambda)
+                assert np.all(np.abs(y - 1.0) <= 2.0 ** -23)
 
 
 def test_edge_lengths_bf16(gpu, oracle_mod):
