@@ -112,15 +112,23 @@ TP_API int softmax_tp_stream_scale_f32(const float *x, float *y, float a, int64_
 /* ----- planning, workspace, tuning (host side) ----- */
 
 typedef struct {
-    int32_t path;           /* 1: one workgroup per row, single launch; 2: rows cut into chunks */
-    int32_t block;          /* threads per workgroup */
-    int32_t unroll;         /* 16-byte loads in flight per thread */
-    int32_t vector_elems;   /* elements per access: 4 (fp32) / 8 (bf16), or 1 when unaligned */
-    int32_t merge_kernel;   /* path 2: 1 if partial results are merged by a kernel of their own,
-                               0 if each workgroup of the next pass merges them itself */
-    int32_t launches;       /* kernel launches of the Two-Pass call */
-    int64_t chunk_vecs;     /* path 2: 16-byte vectors per chunk */
-    int64_t chunks;         /* path 2: chunks per row */
+    int32_t block;      /* threads per workgroup */
+    int32_t unroll;     /* 16-byte loads in flight per thread */
+    int64_t chunk_vecs; /* 16-byte vectors per workgroup (0 on the rows path: the whole row) */
+    int64_t chunks;     /* workgroups per row */
+} softmax_tp_shape_t;
+
+typedef struct {
+    int32_t path;          /* 1: one workgroup per row, every pass in a single launch;
+                              2: rows cut into chunks, one launch per pass + small merge launches */
+    int32_t vector_elems;  /* elements per access: 4 (fp32) / 8 (bf16), or 1 when unaligned */
+    int32_t launches;      /* kernel launches of the Two-Pass call */
+    int32_t nt_first_load; /* path 2: 1 if even the first read of x carries the non-temporal hint
+                              (input too large for any cache to help the second read) */
+    softmax_tp_shape_t rows;    /* path 1 */
+    softmax_tp_shape_t reduce;  /* path 2, read-only passes (Two-Pass pass 1; max; sum-exp) */
+    softmax_tp_shape_t map;     /* path 2, read-write passes (Two-Pass pass 2; exp-scale; scale) */
+    softmax_tp_shape_t mapsum;  /* path 2, the read-write pass that also reduces (exp-store) */
     int64_t workspace_bytes;
 } softmax_tp_plan_t;
 
@@ -129,13 +137,22 @@ typedef struct {
  * whether x and y are congruent modulo 16 bytes.  Pure host logic: no GPU needed.
  */
 TP_API int softmax_tp_plan(int64_t rows, int64_t n, int32_t elem_bytes, int32_t congruent16,
-                    softmax_tp_plan_t *plan);
+                           softmax_tp_plan_t *plan);
 
 /*
- * Overrides a planner parameter (for sweeps): "path" (0 auto, 1, 2), "block_rows",
- * "unroll_rows", "block_chunk", "unroll_chunk", "target_chunks" (workgroups aimed
- * for on path 2), "min_chunk_vecs", "fold_max" (largest chunk count merged inside
- * the next pass).  value 0 restores the default.  Not thread safe against running calls.
+ * Overrides a planner parameter (for sweeps).  Keys:
+ *   "path"            0 auto, 1 rows path, 2 chunk path
+ *   "block_rows", "unroll_rows"          shape on the rows path
+ *   "block_reduce", "unroll_reduce", "target_reduce"  read-only passes: shape and the
+ *                     number of workgroups aimed for over the whole launch
+ *   "block_map", "unroll_map", "tiles_map"  read-write passes: shape and tiles
+ *                     (block * unroll vectors) per workgroup
+ *   "block_mapsum", "unroll_mapsum", "tiles_mapsum"  the same for the exp-store pass
+ *   "direction"       1: every pass walks memory forwards; 2 (default): successive
+ *                     passes alternate direction
+ *   "nt_first"        1: first read of x cacheable; 2: non-temporal; default: by size
+ * block is 256, 512 or 1024; unroll 2, 4 or 8 (bf16: 2 or 4).  value 0 restores the
+ * default.  Not thread safe against running calls.
  */
 TP_API int softmax_tp_tune(const char *key, int64_t value);
 

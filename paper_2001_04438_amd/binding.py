@@ -38,23 +38,47 @@ ENTRY_POINTS = {
 TP_ERR_NULL, TP_ERR_NEGATIVE, TP_ERR_TOO_LARGE, TP_ERR_ALIGN, TP_ERR_TUNING = -1, -2, -3, -4, -5
 
 
+class Shape(ctypes.Structure):
+    """Mirror of softmax_tp_shape_t."""
+
+    _fields_ = [("block", ctypes.c_int32), ("unroll", ctypes.c_int32),
+                ("chunk_vecs", _i64), ("chunks", _i64)]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
 class Plan(ctypes.Structure):
     """Mirror of softmax_tp_plan_t."""
 
     _fields_ = [
         ("path", ctypes.c_int32),
-        ("block", ctypes.c_int32),
-        ("unroll", ctypes.c_int32),
         ("vector_elems", ctypes.c_int32),
-        ("merge_kernel", ctypes.c_int32),
         ("launches", ctypes.c_int32),
-        ("chunk_vecs", _i64),
-        ("chunks", _i64),
+        ("nt_first_load", ctypes.c_int32),
+        ("rows", Shape),
+        ("reduce", Shape),
+        ("map", Shape),
+        ("mapsum", Shape),
         ("workspace_bytes", _i64),
     ]
 
     def as_dict(self):
-        return {k: getattr(self, k) for k, _ in self._fields_}
+        d = {}
+        for k, _ in self._fields_:
+            v = getattr(self, k)
+            d[k] = v.as_dict() if isinstance(v, Shape) else v
+        if self.path == 1:
+            for k in ("reduce", "map", "mapsum"):
+                d.pop(k)
+        else:
+            d.pop("rows")
+        return d
+
+
+TUNE_KEYS = ("path", "block_rows", "unroll_rows", "block_reduce", "unroll_reduce", "target_reduce",
+             "block_map", "unroll_map", "tiles_map", "block_mapsum", "unroll_mapsum", "tiles_mapsum",
+             "direction", "nt_first")
 
 
 class SoftmaxTpError(RuntimeError):
@@ -168,6 +192,12 @@ def softmax_tp_plan(rows, n, elem_bytes=4, congruent16=True) -> Plan:
 
 def softmax_tp_tune(key: str, value: int):
     _check("softmax_tp_tune", lib().softmax_tp_tune(key.encode(), int(value)))
+
+
+def softmax_tp_tune_reset():
+    """Restores every planner parameter to its default."""
+    for key in TUNE_KEYS:
+        softmax_tp_tune(key, 0)
 
 
 def softmax_tp_release():

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libsoftmax_tp.so")
 SOURCES = ["softmax_tp.hip"]
-HEADERS = ["tp_device.h", "extexp.h", "expconst.h", os.path.join("..", "..", "include", "softmax_tp.h")]
+HEADERS = ["tp_kernels.h", "tp_device.h", "extexp.h", "expconst.h", os.path.join("..", "..", "include", "softmax_tp.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -331,8 +331,10 @@ __device__ __forceinline__ void st(VEC *p, VEC v)
 // loads in flight; consecutive lanes touch consecutive vectors, so one wave
 // instruction moves 1 KiB contiguously.  P provides
 //     static constexpr bool kWrite;
-//     template <int G, int V, bool MASKED> void group(const float *f, float *o, const bool *ok);
-// where f/o hold G = U*V elements and ok[u] says whether vector u is real.
+//     template <int G> void group(const float *f, float *o);
+// which consumes G elements (and, if kWrite, produces G outputs).  Full rounds
+// hand over G = U*V elements at once; the last, partly filled round hands over
+// the vectors that exist one at a time.
 template <class IO, int BLOCK, int U, bool NT_LOAD, bool NT_STORE, class P>
 __device__ __forceinline__ void stream(const Seg<IO> &s, P &p)
 {
@@ -353,7 +355,7 @@ __device__ __forceinline__ void stream(const Seg<IO> &s, P &p)
 #pragma unroll
         for (int u = 0; u < U; ++u)
             IO::unpack(v[u], f + u * V);
-        p.template group<G, V, false>(f, o, nullptr);
+        p.template group<G>(f, o);
         if constexpr (P::kWrite) {
 #pragma unroll
             for (int u = 0; u < U; ++u)
@@ -368,16 +370,15 @@ __device__ __forceinline__ void stream(const Seg<IO> &s, P &p)
             ok[u] = k + (uint32_t)(u * BLOCK) < cnt;
             v[u] = ok[u] ? ld<NT_LOAD>(xb + (k + (uint32_t)(u * BLOCK))) : IO::zero();
         }
-        float f[G], o[G];
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-            IO::unpack(v[u], f + u * V);
-        p.template group<G, V, true>(f, o, ok);
-        if constexpr (P::kWrite) {
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (ok[u])
-                    st<NT_STORE>(yb + (k + (uint32_t)(u * BLOCK)), IO::pack(o + u * V));
+        for (int u = 0; u < U; ++u) {
+            if (ok[u]) {
+                float f[V], o[V];
+                IO::unpack(v[u], f);
+                p.template group<V>(f, o);
+                if constexpr (P::kWrite)
+                    st<NT_STORE>(yb + (k + (uint32_t)(u * BLOCK)), IO::pack(o));
+            }
         }
     }
     if (s.edges) {
@@ -387,7 +388,7 @@ __device__ __forceinline__ void stream(const Seg<IO> &s, P &p)
             const int64_t i = (int)threadIdx.x < s.head ? (int64_t)threadIdx.x
                                                         : s.tail0 + ((int64_t)threadIdx.x - s.head);
             float f = IO::load1(s.xrow + i), o;
-            p.template group<1, 1, false>(&f, &o, nullptr);
+            p.template group<1>(&f, &o);
             if constexpr (P::kWrite)
                 IO::store1(s.yrow + i, o);
         }
@@ -414,18 +415,14 @@ __device__ __forceinline__ float tree_sum(float *v)
 struct PairSum {
     static constexpr bool kWrite = false;
     float m = 0.f, n = kNIdent;
-    template <int G, int V, bool MASKED>
-    __device__ __forceinline__ void group(const float *f, float *, const bool *ok)
+    template <int G>
+    __device__ __forceinline__ void group(const float *f, float *)
     {
         float mi[G], ni[G];
         float nmax = n;
 #pragma unroll
         for (int i = 0; i < G; ++i) {
             tp_extexp(f[i], &mi[i], &ni[i]);
-            if (MASKED && !ok[i / V]) {
-                mi[i] = 0.f;
-                ni[i] = kNIdent;
-            }
             nmax = fmaxf(nmax, ni[i]);
         }
         float acc = scale_pow2(m, n - nmax);
@@ -441,8 +438,8 @@ struct PairSum {
 struct PairOut {
     static constexpr bool kWrite = true;
     float lambda, n_sum;
-    template <int G, int V, bool MASKED>
-    __device__ __forceinline__ void group(const float *f, float *o, const bool *)
+    template <int G>
+    __device__ __forceinline__ void group(const float *f, float *o)
     {
 #pragma unroll
         for (int i = 0; i < G; ++i) {
@@ -457,13 +454,12 @@ struct PairOut {
 struct MaxOf {
     static constexpr bool kWrite = false;
     float mx = -__builtin_inff();
-    template <int G, int V, bool MASKED>
-    __device__ __forceinline__ void group(const float *f, float *, const bool *ok)
+    template <int G>
+    __device__ __forceinline__ void group(const float *f, float *)
     {
 #pragma unroll
         for (int i = 0; i < G; ++i)
-            if (!MASKED || ok[i / V])
-                mx = fmaxf(mx, f[i]);
+            mx = fmaxf(mx, f[i]);
     }
 };
 
@@ -472,16 +468,13 @@ struct SumExp {
     static constexpr bool kWrite = false;
     float mu;
     float s = 0.f;
-    template <int G, int V, bool MASKED>
-    __device__ __forceinline__ void group(const float *f, float *, const bool *ok)
+    template <int G>
+    __device__ __forceinline__ void group(const float *f, float *)
     {
         float e[G];
 #pragma unroll
-        for (int i = 0; i < G; ++i) {
+        for (int i = 0; i < G; ++i)
             e[i] = exp_nonpos(f[i] - mu);
-            if (MASKED && !ok[i / V])
-                e[i] = 0.f;
-        }
         s += tree_sum<G>(e);
     }
 };
@@ -490,8 +483,8 @@ struct SumExp {
 struct ExpScale {
     static constexpr bool kWrite = true;
     float mu, lambda;
-    template <int G, int V, bool MASKED>
-    __device__ __forceinline__ void group(const float *f, float *o, const bool *)
+    template <int G>
+    __device__ __forceinline__ void group(const float *f, float *o)
     {
 #pragma unroll
         for (int i = 0; i < G; ++i)
@@ -504,15 +497,13 @@ struct ExpStoreSum {
     static constexpr bool kWrite = true;
     float mu;
     float s = 0.f;
-    template <int G, int V, bool MASKED>
-    __device__ __forceinline__ void group(const float *f, float *o, const bool *ok)
+    template <int G>
+    __device__ __forceinline__ void group(const float *f, float *o)
     {
         float e[G];
 #pragma unroll
-        for (int i = 0; i < G; ++i) {
-            o[i] = exp_nonpos(f[i] - mu);
-            e[i] = (MASKED && !ok[i / V]) ? 0.f : o[i];
-        }
+        for (int i = 0; i < G; ++i)
+            e[i] = o[i] = exp_nonpos(f[i] - mu);
         s += tree_sum<G>(e);
     }
 };
@@ -521,8 +512,8 @@ struct ExpStoreSum {
 struct Scale {
     static constexpr bool kWrite = true;
     float lambda;
-    template <int G, int V, bool MASKED>
-    __device__ __forceinline__ void group(const float *f, float *o, const bool *)
+    template <int G>
+    __device__ __forceinline__ void group(const float *f, float *o)
     {
 #pragma unroll
         for (int i = 0; i < G; ++i)
@@ -534,21 +525,21 @@ struct Scale {
 struct SumOf {
     static constexpr bool kWrite = false;
     float s = 0.f;
-    template <int G, int V, bool MASKED>
-    __device__ __forceinline__ void group(const float *f, float *, const bool *ok)
+    template <int G>
+    __device__ __forceinline__ void group(const float *f, float *)
     {
         float e[G];
 #pragma unroll
         for (int i = 0; i < G; ++i)
-            e[i] = (MASKED && !ok[i / V]) ? 0.f : f[i];
+            e[i] = f[i];
         s += tree_sum<G>(e);
     }
 };
 
 struct Copy {
     static constexpr bool kWrite = true;
-    template <int G, int V, bool MASKED>
-    __device__ __forceinline__ void group(const float *f, float *o, const bool *)
+    template <int G>
+    __device__ __forceinline__ void group(const float *f, float *o)
     {
 #pragma unroll
         for (int i = 0; i < G; ++i)

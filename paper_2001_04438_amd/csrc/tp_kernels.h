@@ -1,0 +1,279 @@
+// The __global__ kernels of the softmax library (gfx950).
+//
+// rows path   rows_*: one workgroup owns a whole row and runs every pass of the
+//             algorithm in one launch; the re-read of the row comes from L2.
+// chunk path  chunk_*: a row is cut into chunks, one workgroup each.  A reducing
+//             pass leaves one partial result per chunk; merge_* folds the partials
+//             of every row into one value that the next pass reads.
+#pragma once
+#include "tp_device.h"
+
+namespace tp {
+
+// Cache hints.  A load whose data the next pass reads again stays cacheable; the
+// last read of x and the stores of y carry the non-temporal hint so that they do
+// not displace it.  On the chunk path the first read is non-temporal as well when
+// the input is far larger than the caches (template parameter NT_FIRST).
+constexpr bool kLoadKeep = false, kLoadStream = true;
+constexpr bool kStoreKeep = false, kStoreStream = true;
+constexpr uint32_t kXcds = 8;  // workgroup i is dispatched to XCD i % 8, each with its own L2
+
+// ---- rows path: grid = rows ------------------------------------------------
+
+template <class IO, int BLOCK, int U>
+__global__ __launch_bounds__(BLOCK) void rows_2p(const typename IO::elem *x,
+                                                 typename IO::elem *y, int64_t n)
+{
+    __shared__ float lds[2 * kMaxWaves];
+    const Seg<IO> s = make_seg<IO>(x, y, n, blockIdx.x, 0, INT64_MAX / 2);
+    PairSum acc;
+    stream<IO, BLOCK, U, kLoadKeep, kStoreStream>(s, acc);
+    block_pair<BLOCK>(acc.m, acc.n, lds);
+    PairOut out{1.0f / acc.m, acc.n};
+    stream<IO, BLOCK, U, kLoadStream, kStoreStream>(s, out);
+}
+
+template <class IO, int BLOCK, int U>
+__global__ __launch_bounds__(BLOCK) void rows_3p_recompute(const typename IO::elem *x,
+                                                           typename IO::elem *y, int64_t n)
+{
+    __shared__ float lds[2 * kMaxWaves];
+    const Seg<IO> s = make_seg<IO>(x, y, n, blockIdx.x, 0, INT64_MAX / 2);
+    MaxOf mx;
+    stream<IO, BLOCK, U, kLoadKeep, kStoreStream>(s, mx);
+    const float mu = block_max<BLOCK>(mx.mx, lds);
+    SumExp se{mu};
+    stream<IO, BLOCK, U, kLoadKeep, kStoreStream>(s, se);
+    const float sigma = block_sum<BLOCK>(se.s, lds);
+    ExpScale es{mu, 1.0f / sigma};
+    stream<IO, BLOCK, U, kLoadStream, kStoreStream>(s, es);
+}
+
+template <class IO, int BLOCK, int U>
+__global__ __launch_bounds__(BLOCK) void rows_3p_reload(const typename IO::elem *x,
+                                                        typename IO::elem *y, int64_t n)
+{
+    __shared__ float lds[2 * kMaxWaves];
+    const Seg<IO> s = make_seg<IO>(x, y, n, blockIdx.x, 0, INT64_MAX / 2);
+    MaxOf mx;
+    stream<IO, BLOCK, U, kLoadKeep, kStoreStream>(s, mx);
+    const float mu = block_max<BLOCK>(mx.mx, lds);
+    ExpStoreSum ess{mu};
+    stream<IO, BLOCK, U, kLoadStream, kStoreKeep>(s, ess);  // y is read back by the next pass
+    const float sigma = block_sum<BLOCK>(ess.s, lds);
+    // each thread re-reads exactly the vectors it stored itself, so program order suffices
+    const Seg<IO> sy = make_seg<IO>(y, y, n, blockIdx.x, 0, INT64_MAX / 2);
+    Scale sc{1.0f / sigma};
+    stream<IO, BLOCK, U, kLoadStream, kStoreStream>(sy, sc);
+}
+
+// ---- chunk path: grid = rows * chunks, rounded up to a multiple of kXcds ---------
+
+struct ChunkArgs {
+    int64_t n;
+    int64_t chunk_vecs;
+    int32_t chunks;
+    uint32_t total;   // rows * chunks
+    int32_t reverse;  // walk the chunks from the last to the first
+};
+
+// Successive passes walk memory in opposite directions, so a pass starts on the
+// data the previous one touched last (still in L2 / the memory-side cache).  The
+// reversal permutes groups of kXcds workgroups and keeps the position inside the
+// group, so a chunk is handled by the same XCD - the same L2 - in both directions.
+#define TP_CHUNK_PROLOGUE                                                  \
+    uint32_t wg = blockIdx.x;                                              \
+    if (a.reverse)                                                         \
+        wg = (gridDim.x / kXcds - 1 - wg / kXcds) * kXcds + wg % kXcds;    \
+    if (wg >= a.total)                                                     \
+        return;                                                            \
+    const int64_t row = wg / (uint32_t)a.chunks;                           \
+    const int64_t chunk = wg % (uint32_t)a.chunks;
+
+// Two-Pass pass 1: one (m, n) pair per chunk.
+template <class IO, int BLOCK, int U, bool NT_FIRST>
+__global__ __launch_bounds__(BLOCK) void chunk_2p_pass1(const typename IO::elem *x, ChunkArgs a,
+                                                        float2 *partial)
+{
+    __shared__ float lds[2 * kMaxWaves];
+    TP_CHUNK_PROLOGUE
+    const Seg<IO> s = make_seg<IO>(x, nullptr, a.n, row, chunk, a.chunk_vecs);
+    PairSum acc;
+    stream<IO, BLOCK, U, NT_FIRST, kStoreStream>(s, acc);
+    block_pair<BLOCK>(acc.m, acc.n, lds);
+    if (threadIdx.x == 0)
+        partial[wg] = make_float2(acc.m, acc.n);
+}
+
+// Two-Pass pass 2: pairs[row] = (m_sum, n_sum) of the row.
+template <class IO, int BLOCK, int U>
+__global__ __launch_bounds__(BLOCK) void chunk_2p_pass2(const typename IO::elem *x,
+                                                        typename IO::elem *y, ChunkArgs a,
+                                                        const float2 *pairs)
+{
+    TP_CHUNK_PROLOGUE
+    const float2 q = pairs[row];
+    const Seg<IO> s = make_seg<IO>(x, y, a.n, row, chunk, a.chunk_vecs);
+    PairOut out{1.0f / q.x, q.y};
+    stream<IO, BLOCK, U, kLoadStream, kStoreStream>(s, out);
+}
+
+template <class IO, int BLOCK, int U, bool NT_FIRST>
+__global__ __launch_bounds__(BLOCK) void chunk_max(const typename IO::elem *x, ChunkArgs a,
+                                                   float *pmax)
+{
+    __shared__ float lds[2 * kMaxWaves];
+    TP_CHUNK_PROLOGUE
+    const Seg<IO> s = make_seg<IO>(x, nullptr, a.n, row, chunk, a.chunk_vecs);
+    MaxOf mx;
+    stream<IO, BLOCK, U, NT_FIRST, kStoreStream>(s, mx);
+    const float v = block_max<BLOCK>(mx.mx, lds);
+    if (threadIdx.x == 0)
+        pmax[wg] = v;
+}
+
+template <class IO, int BLOCK, int U, bool NT_FIRST>
+__global__ __launch_bounds__(BLOCK) void chunk_sumexp(const typename IO::elem *x, ChunkArgs a,
+                                                      const float *rowmax, float *psum)
+{
+    __shared__ float lds[2 * kMaxWaves];
+    TP_CHUNK_PROLOGUE
+    const Seg<IO> s = make_seg<IO>(x, nullptr, a.n, row, chunk, a.chunk_vecs);
+    SumExp se{rowmax[row]};
+    stream<IO, BLOCK, U, NT_FIRST, kStoreStream>(s, se);
+    const float v = block_sum<BLOCK>(se.s, lds);
+    if (threadIdx.x == 0)
+        psum[wg] = v;
+}
+
+template <class IO, int BLOCK, int U>
+__global__ __launch_bounds__(BLOCK) void chunk_expscale(const typename IO::elem *x,
+                                                        typename IO::elem *y, ChunkArgs a,
+                                                        const float *rowmax, const float *rowsum)
+{
+    TP_CHUNK_PROLOGUE
+    const Seg<IO> s = make_seg<IO>(x, y, a.n, row, chunk, a.chunk_vecs);
+    ExpScale es{rowmax[row], 1.0f / rowsum[row]};
+    stream<IO, BLOCK, U, kLoadStream, kStoreStream>(s, es);
+}
+
+template <class IO, int BLOCK, int U>
+__global__ __launch_bounds__(BLOCK) void chunk_expstore(const typename IO::elem *x,
+                                                        typename IO::elem *y, ChunkArgs a,
+                                                        const float *rowmax, float *psum)
+{
+    __shared__ float lds[2 * kMaxWaves];
+    TP_CHUNK_PROLOGUE
+    const Seg<IO> s = make_seg<IO>(x, y, a.n, row, chunk, a.chunk_vecs);
+    ExpStoreSum ess{rowmax[row]};
+    stream<IO, BLOCK, U, kLoadStream, kStoreKeep>(s, ess);
+    const float v = block_sum<BLOCK>(ess.s, lds);
+    if (threadIdx.x == 0)
+        psum[wg] = v;
+}
+
+// y = x / rowsum[row] (reload pass 3, x == y); with rowsum == nullptr: y = lambda * x.
+template <class IO, int BLOCK, int U>
+__global__ __launch_bounds__(BLOCK) void chunk_scale(const typename IO::elem *x,
+                                                     typename IO::elem *y, ChunkArgs a,
+                                                     const float *rowsum, float lambda)
+{
+    TP_CHUNK_PROLOGUE
+    if (rowsum)
+        lambda = 1.0f / rowsum[row];
+    const Seg<IO> s = make_seg<IO>(x, y, a.n, row, chunk, a.chunk_vecs);
+    Scale sc{lambda};
+    stream<IO, BLOCK, U, kLoadStream, kStoreStream>(s, sc);
+}
+
+// Calibration streams built from the same parts.
+template <class IO, int BLOCK, int U>
+__global__ __launch_bounds__(BLOCK) void chunk_read(const typename IO::elem *x, ChunkArgs a,
+                                                    float *psum)
+{
+    __shared__ float lds[2 * kMaxWaves];
+    TP_CHUNK_PROLOGUE
+    const Seg<IO> s = make_seg<IO>(x, nullptr, a.n, row, chunk, a.chunk_vecs);
+    SumOf so;
+    stream<IO, BLOCK, U, kLoadStream, kStoreStream>(s, so);
+    const float v = block_sum<BLOCK>(so.s, lds);
+    if (threadIdx.x == 0)
+        psum[wg] = v;
+}
+
+template <class IO, int BLOCK, int U>
+__global__ __launch_bounds__(BLOCK) void chunk_copy(const typename IO::elem *x,
+                                                    typename IO::elem *y, ChunkArgs a)
+{
+    TP_CHUNK_PROLOGUE
+    const Seg<IO> s = make_seg<IO>(x, y, a.n, row, chunk, a.chunk_vecs);
+    Copy cp;
+    stream<IO, BLOCK, U, kLoadStream, kStoreStream>(s, cp);
+}
+
+// ---- merges: grid = rows, one workgroup folds the `chunks` partials of its row ----
+
+constexpr int kMergeBlock = 256;
+
+__global__ __launch_bounds__(kMergeBlock) void merge_pairs_kernel(const float2 *partial, int chunks,
+                                                                  float2 *out)
+{
+    __shared__ float lds[2 * kMaxWaves];
+    const float2 *p = partial + (int64_t)blockIdx.x * chunks;
+    float m = 0.f, n = kNIdent;
+    for (int i = threadIdx.x; i < chunks; i += kMergeBlock) {
+        const float2 q = p[i];
+        const float nmax = fmaxf(n, q.y);
+        m = scale_pow2(m, n - nmax) + scale_pow2(q.x, q.y - nmax);
+        n = nmax;
+    }
+    block_pair<kMergeBlock>(m, n, lds);
+    if (threadIdx.x == 0)
+        out[blockIdx.x] = make_float2(m, n);
+}
+
+__global__ __launch_bounds__(kMergeBlock) void merge_max_kernel(const float *partial, int chunks,
+                                                                float *out)
+{
+    __shared__ float lds[2 * kMaxWaves];
+    const float *p = partial + (int64_t)blockIdx.x * chunks;
+    float v = -__builtin_inff();
+    for (int i = threadIdx.x; i < chunks; i += kMergeBlock)
+        v = fmaxf(v, p[i]);
+    v = block_max<kMergeBlock>(v, lds);
+    if (threadIdx.x == 0)
+        out[blockIdx.x] = v;
+}
+
+__global__ __launch_bounds__(kMergeBlock) void merge_sum_kernel(const float *partial, int chunks,
+                                                                float *out)
+{
+    __shared__ float lds[2 * kMaxWaves];
+    const float *p = partial + (int64_t)blockIdx.x * chunks;
+    float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;  // four loads in flight per thread
+    int i = threadIdx.x;
+    for (; i + 3 * kMergeBlock < chunks; i += 4 * kMergeBlock) {
+        v0 += p[i];
+        v1 += p[i + kMergeBlock];
+        v2 += p[i + 2 * kMergeBlock];
+        v3 += p[i + 3 * kMergeBlock];
+    }
+    for (; i < chunks; i += kMergeBlock)
+        v0 += p[i];
+    const float v = block_sum<kMergeBlock>((v0 + v1) + (v2 + v3), lds);
+    if (threadIdx.x == 0)
+        out[blockIdx.x] = v;
+}
+
+// ---- ExtExp alone ------------------------------------------------------------
+
+__global__ __launch_bounds__(256) void extexp_kernel(const float *x, float *m, float *e,
+                                                     int64_t count)
+{
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t step = (int64_t)gridDim.x * 256;
+    for (; i < count; i += step)
+        tp_extexp(x[i], &m[i], &e[i]);
+}
+
+}  // namespace tp

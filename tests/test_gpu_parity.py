@@ -31,9 +31,7 @@ def gpu():
     assert torch.cuda.is_available(), "these tests need the MI355X"
     binding.lib()  # raises if the HIP library has not been built
     yield binding
-    for key in ("path", "block_rows", "unroll_rows", "block_chunk", "unroll_chunk",
-                "target_chunks", "min_chunk_vecs", "fold_max"):
-        binding.softmax_tp_tune(key, 0)
+    binding.softmax_tp_tune_reset()
     binding.softmax_tp_release()
 
 
@@ -104,16 +102,16 @@ def test_cfg2_rows_path(gpu, oracle_mod, name, tol):
 def test_cfg3_chunk_path(gpu, oracle_mod, name, tol):
     x = workloads.cfg3(rows=3, n=1_000_000)
     plan = gpu.softmax_tp_plan(3, 1_000_000)
-    assert plan.path == 2 and plan.chunks > 1
+    assert plan.path == 2 and plan.reduce.chunks > 1 and plan.map.chunks > plan.reduce.chunks
     _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
 
 
 @pytest.mark.parametrize("name,tol", ALGOS_F32)
 def test_cfg4_single_long_vector(gpu, oracle_mod, name, tol):
-    n = (1 << 23) + 3  # several hundred chunks, merge kernel, ragged tail
+    n = (1 << 23) + 3  # thousands of chunks, ragged tail
     x = workloads.cfg4(n=n)
     plan = gpu.softmax_tp_plan(1, n)
-    assert plan.path == 2 and plan.merge_kernel == 1
+    assert plan.path == 2 and plan.reduce.chunks >= 512 and plan.map.chunks >= 2048
     c = _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
     assert c.n_normal < x.size // 100  # almost everything underflows next to the outliers
 
@@ -314,33 +312,33 @@ def test_launch_shapes(gpu, oracle_mod):
             gpu.softmax_tp_tune("path", path)
             for block in (256, 512, 1024):
                 for unroll in (2, 4, 8):
-                    for key in ("block_rows", "block_chunk"):
+                    for key in ("block_rows", "block_reduce", "block_map", "block_mapsum"):
                         gpu.softmax_tp_tune(key, block)
-                    for key in ("unroll_rows", "unroll_chunk"):
+                    for key in ("unroll_rows", "unroll_reduce", "unroll_map", "unroll_mapsum"):
                         gpu.softmax_tp_tune(key, unroll)
                     for name, tol in ALGOS_F32:
                         _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
                     if unroll < 8:
                         _check(oracle_mod, xb, _run(gpu.softmax2p_bf16io, xb), TOL_BF16, bf16=True)
-                    else:
+                    else:  # bf16 keeps at most four 16-byte loads in flight
                         with pytest.raises(gpu.SoftmaxTpError):
                             _run(gpu.softmax2p_bf16io, xb)
-        # chunk path with the partials merged by the separate kernel vs inside pass 2
+        # chunk path: many small chunks vs few large ones, every direction / hint setting
+        gpu.softmax_tp_tune_reset()
         gpu.softmax_tp_tune("path", 2)
-        gpu.softmax_tp_tune("block_chunk", 256)
-        gpu.softmax_tp_tune("unroll_chunk", 2)
-        gpu.softmax_tp_tune("min_chunk_vecs", 512)
-        outs = []
-        for fold in (1, 1000):
-            gpu.softmax_tp_tune("fold_max", fold)
-            assert gpu.softmax_tp_plan(4, 50_003).merge_kernel == (1 if fold == 1 else 0)
-            outs.append([_run(getattr(gpu, name), x) for name, _ in ALGOS_F32])
-        for a, b in zip(*outs):
-            assert np.array_equal(a, b)
+        for direction in (1, 2):
+            for nt_first in (1, 2):
+                for target, tiles in ((64, 1), (100_000, 3)):
+                    gpu.softmax_tp_tune("direction", direction)
+                    gpu.softmax_tp_tune("nt_first", nt_first)
+                    gpu.softmax_tp_tune("target_reduce", target)
+                    gpu.softmax_tp_tune("tiles_map", tiles)
+                    gpu.softmax_tp_tune("tiles_mapsum", tiles)
+                    for name, tol in ALGOS_F32:
+                        _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
+                    _check(oracle_mod, xb, _run(gpu.softmax2p_bf16io, xb), TOL_BF16, bf16=True)
     finally:
-        for key in ("path", "block_rows", "unroll_rows", "block_chunk", "unroll_chunk",
-                    "min_chunk_vecs", "fold_max"):
-            gpu.softmax_tp_tune(key, 0)
+        gpu.softmax_tp_tune_reset()
 
 
 def test_bitwise_reproducible(gpu):
