@@ -31,7 +31,7 @@ static Tuning g_tune;
 constexpr int64_t kRowsPathMaxBytes = 256 * 1024;  // longest row one workgroup takes
 constexpr int64_t kRowsPathMinRows = 32;           // fewer rows than this cannot fill the chip
 constexpr int64_t kSmallRowBytes = 32 * 1024;      // ... unless the rows are this short
-constexpr int64_t kTargetReduce = 2048;            // workgroups of a read-only pass (8 per CU)
+constexpr int64_t kTargetReduce = 1024;            // workgroups of a read-only pass (4 per CU)
 constexpr int64_t kNtFirstBytes = (int64_t)512 << 20;  // inputs beyond this outlive every cache
 constexpr int64_t kGridMax = 0x7FFFFFF0;           // grids are rounded up to a multiple of kXcds
 constexpr int64_t kChunkVecsMax = (int64_t)1 << 26;  // a chunk is indexed with 32-bit offsets
@@ -131,11 +131,12 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
         int rc = chunk_shape(rows, nvec, block, unroll, (nvec + per_row - 1) / per_row, &p->reduce);
         if (rc != TP_OK) return rc;
     }
-    // read-write passes: one tile per workgroup, so no workgroup ever waits on its own stores
+    // read-write passes: many short-lived workgroups (two rounds each), so that hardly any
+    // load has to queue behind the stores of an earlier round of the same wave
     {
         const int block = g_tune.block_map ? (int)g_tune.block_map : 512;
         const int unroll = g_tune.unroll_map ? (int)g_tune.unroll_map : 2;
-        const int64_t tiles = g_tune.tiles_map ? g_tune.tiles_map : 1;
+        const int64_t tiles = g_tune.tiles_map ? g_tune.tiles_map : 2;
         int rc = chunk_shape(rows, nvec, block, unroll, tiles * block * unroll, &p->map);
         if (rc != TP_OK) return rc;
     }

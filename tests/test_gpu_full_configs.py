@@ -1,0 +1,76 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+The oracle's streaming comparator checks every element (it needs no stored copy of p, so even
+the 2^28-element vector is compared in full), on all five configurations and all variants."""
+import numpy as np
+import pytest
+
+from paper_2001_04438_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2001_04438_amd import binding
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    binding.lib()
+    binding.softmax_tp_tune_reset()
+    yield binding
+    binding.softmax_tp_release()
+
+
+def _run(fn, x):
+    import torch
+    rows, n = x.shape
+    flat = x.reshape(-1)
+    xd = torch.from_numpy(flat.view(np.int16) if flat.dtype == np.uint16 else flat).cuda()
+    yd = torch.empty_like(xd)
+    fn(xd, yd, rows, n)
+    torch.cuda.synchronize()
+    y = yd.cpu().numpy()
+    del xd, yd
+    torch.cuda.empty_cache()
+    return (y.view(np.uint16) if flat.dtype == np.uint16 else y).reshape(rows, n)
+
+
+F32 = [("softmax2p_f32", 4e-6), ("softmax3p_recompute_f32", 1e-5), ("softmax3p_reload_f32", 1e-5)]
+
+
+@pytest.mark.parametrize("cfg", ["cfg2", "cfg3", "cfg4"])
+def test_full_size_fp32(gpu, oracle_mod, cfg):
+    x = workloads.make(cfg)
+    rows, n = x.shape
+    print(f"{cfg}: {rows} x {n}", flush=True)
+    for name, tol in F32:
+        y = _run(getattr(gpu, name), x)
+        c = oracle_mod.compare(x, y, tol)
+        print(f"  {name}: max_rel_err={c.max_rel_err:.3e} row_sum_dev={c.max_row_sum_dev:.3e}", flush=True)
+        assert c.n_total == x.size and c.ok(), (name, c.as_dict())
+        assert c.max_row_sum_dev <= tol + n * 2.0 ** -126
+
+
+def test_full_size_cfg4_structure(gpu):
+    """Properties that hold whatever the size: only entries within ~87 of the maximum can be
+    non-zero, the largest input gets the largest output, outputs are ordered like inputs."""
+    x = workloads.make("cfg4")
+    y = _run(gpu.softmax2p_f32, x)[0]
+    x = x[0]
+    top = float(x.max())
+    assert y[np.argmax(x)] == y.max() > 0
+    assert np.all(y[x < top - 104.0] == 0.0)
+    assert np.all(y[x > top - 80.0] > 0.0)
+    idx = np.flatnonzero(x > top - 80.0)
+    order = idx[np.argsort(x[idx], kind="stable")]
+    assert np.all(np.diff(y[order]) >= 0)
+    assert abs(float(y.sum(dtype=np.float64)) - 1.0) < 4e-6
+
+
+def test_full_size_bf16(gpu, oracle_mod):
+    x = workloads.make("cfg5")
+    y = _run(gpu.softmax2p_bf16io, x)
+    c = oracle_mod.compare(x, y, 1e-2, bf16=True)
+    print(f"cfg5: max_rel_err={c.max_rel_err:.3e} row_sum_dev={c.max_row_sum_dev:.3e}", flush=True)
+    assert c.n_total == x.size and c.ok(), c.as_dict()
+    assert c.max_row_sum_dev <= 2e-2

@@ -1,0 +1,165 @@
+"""CPU-only checks of the product's host logic: the C ABI loads and exports what the header
+declares, arguments are validated before any GPU call, the launch planner covers every row,
+and the fp32 ExtExp arithmetic (compiled for the host from the kernel's own header) meets the
+accuracy the paper states."""
+import ctypes
+import math
+import os
+import re
+import subprocess
+import sys
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "softmax_tp.h")
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2001_04438_amd import binding, buildlib
+    if not os.path.exists(binding.LIB_PATH):
+        buildlib.build()
+    binding.lib()
+    yield binding
+    binding.softmax_tp_tune_reset()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    return re.findall(r"^TP_API\s+(?:const\s+)?\w+\s*\*?\s*(\w+)\s*\(", text, flags=re.M)
+
+
+def test_library_exports_every_declared_symbol(B):
+    names = declared_symbols()
+    assert len(names) >= 14 and "softmax2p_f32" in names and "softmax2p_bf16io" in names
+    raw = ctypes.CDLL(B.LIB_PATH)
+    for name in names:
+        assert hasattr(raw, name), name
+    assert set(names) == set(B.ENTRY_POINTS)
+
+
+def test_arguments_are_validated_before_any_gpu_call(B):
+    L = B.lib()
+    for fn in (L.softmax2p_f32, L.softmax3p_recompute_f32, L.softmax3p_reload_f32, L.softmax2p_bf16io):
+        assert fn(None, None, 0, 0, None) == 0
+        assert fn(None, None, 0, 10, None) == 0
+        assert fn(None, None, 10, 0, None) == 0
+        assert fn(None, None, -1, 4, None) == B.TP_ERR_NEGATIVE
+        assert fn(None, None, 4, -1, None) == B.TP_ERR_NEGATIVE
+        assert fn(None, 64, 1, 4, None) == B.TP_ERR_NULL
+        assert fn(64, None, 1, 4, None) == B.TP_ERR_NULL
+        assert fn(64, 64, 1 << 40, 1 << 40, None) == B.TP_ERR_TOO_LARGE
+        assert fn(65, 64, 1, 4, None) == B.TP_ERR_ALIGN
+    assert L.softmax2p_f32(66, 64, 1, 4, None) == B.TP_ERR_ALIGN      # fp32 needs 4-byte alignment
+    assert L.softmax_tp_extexp_f32(None, None, None, -3, None) == B.TP_ERR_NEGATIVE
+    assert L.softmax_tp_extexp_f32(None, 64, 64, 3, None) == B.TP_ERR_NULL
+    assert L.softmax2p_f32_pass1(64, None, 1, 4, None) == B.TP_ERR_NULL
+    assert L.softmax2p_f32_pass2(64, None, 64, 1, 4, None) == B.TP_ERR_NULL
+    assert L.softmax2p_f32_pass2(64, 68, 64, 1, 4, None) == B.TP_ERR_ALIGN  # pairs need 8 bytes
+    assert L.softmax_tp_stream_copy_f32(None, 64, 5, None) == B.TP_ERR_NULL
+    assert L.softmax_tp_plan(1, 1, 3, 1, ctypes.byref(B.Plan())) == B.TP_ERR_TUNING
+    assert L.softmax_tp_plan(1, 1, 4, 1, None) == B.TP_ERR_NULL
+    assert B.strerror(B.TP_ERR_ALIGN).startswith("pointer")
+    with pytest.raises(B.SoftmaxTpError):
+        B.softmax2p_f32(None, None, -1, 1, stream=0)
+
+
+CONFIGS = [(1, 4096, 4), (1024, 32768, 4), (64, 1_000_000, 4), (1, 1 << 28, 4), (4096, 21846, 2)]
+
+
+def test_planner_on_the_benchmark_configurations(B):
+    plans = [B.softmax_tp_plan(r, n, s) for r, n, s in CONFIGS]
+    assert [p.path for p in plans] == [1, 1, 2, 2, 1]
+    assert [p.launches for p in plans] == [1, 1, 3, 3, 1]
+    assert plans[1].rows.block == 1024                      # config 2: one workgroup per row
+    assert plans[4].vector_elems == 8 and plans[4].rows.unroll <= 4
+    assert plans[3].nt_first_load == 1 and plans[2].nt_first_load == 0
+    for (rows, n, s), p in zip(CONFIGS, plans):
+        if p.path != 2:
+            continue
+        nvec = -(-n // p.vector_elems)
+        for shape in (p.reduce, p.map, p.mapsum):
+            assert shape.chunk_vecs % (shape.block * shape.unroll) == 0
+            assert shape.chunks * shape.chunk_vecs >= nvec > (shape.chunks - 1) * shape.chunk_vecs
+            assert rows * shape.chunks < 2 ** 31
+        most = max(p.reduce.chunks, p.mapsum.chunks)
+        assert p.workspace_bytes == (2 * rows * most + 2 * rows) * 4
+        assert p.workspace_bytes <= 1 << 20
+
+
+def test_planner_covers_odd_shapes(B):
+    rng = np.random.default_rng(3)
+    for _ in range(300):
+        rows = int(rng.integers(1, 5000))
+        n = int(rng.integers(1, 3_000_000))
+        for s, congruent in ((4, True), (4, False), (2, True), (2, False)):
+            p = B.softmax_tp_plan(rows, n, s, congruent)
+            V = (16 // s) if congruent else 1
+            assert p.vector_elems == V
+            if p.path == 1:
+                assert n * s <= 256 * 1024 and p.rows.block in (256, 512, 1024)
+            else:
+                nvec = -(-n // V)
+                for shape in (p.reduce, p.map, p.mapsum):
+                    assert shape.chunks * shape.chunk_vecs >= nvec
+    assert B.softmax_tp_plan(0, 5).path == 0 and B.softmax_tp_plan(5, 0).path == 0
+    big = B.softmax_tp_plan(1, 1 << 40)
+    assert big.path == 2 and big.map.chunks * big.map.chunk_vecs >= (1 << 38)
+
+
+def test_tuning_keys(B):
+    for key in B.TUNE_KEYS:
+        B.softmax_tp_tune(key, 0)
+    B.softmax_tp_tune("path", 2)
+    assert B.softmax_tp_plan(1024, 32768).path == 2
+    B.softmax_tp_tune("path", 1)
+    assert B.softmax_tp_plan(64, 60_000).path == 1
+    B.softmax_tp_tune("path", 0)
+    B.softmax_tp_tune("block_map", 256)
+    B.softmax_tp_tune("unroll_map", 8)
+    B.softmax_tp_tune("tiles_map", 3)
+    p = B.softmax_tp_plan(2, 10_000_000)
+    assert (p.map.block, p.map.unroll, p.map.chunk_vecs) == (256, 8, 3 * 256 * 8)
+    with pytest.raises(B.SoftmaxTpError):          # bf16 keeps at most 4 loads in flight
+        B.softmax_tp_plan(2, 10_000_000, 2)
+    for key, bad in (("block_map", 300), ("unroll_rows", 3), ("path", 7), ("no_such_key", 1),
+                     ("direction", 3)):
+        with pytest.raises(B.SoftmaxTpError):
+            B.softmax_tp_tune(key, bad)
+    B.softmax_tp_tune_reset()
+    assert B.softmax_tp_plan(2, 10_000_000).map.block == 512
+
+
+def test_constants_header_is_what_the_generator_writes():
+    csrc = os.path.join(ROOT, "paper_2001_04438_amd", "csrc")
+    committed = open(os.path.join(csrc, "expconst.h")).read()
+    out = subprocess.run([sys.executable, os.path.join(csrc, "gen_expconst.py")], check=True,
+                         capture_output=True, text=True).stdout
+    assert out.strip() == committed.strip()
+    assert open(os.path.join(csrc, "expconst.h")).read() == committed
+
+
+def test_fp32_extexp_accuracy_on_the_host(tmp_path):
+    """Section 6.3 states a maximum error under 2 ULP over all valid inputs.  The kernel's
+    evaluator header is compiled with gcc (fmaf / rintf are exact on the host too) and swept
+    against 80-bit expl: every 9th fp32 value in [-104, 89] by default, every value with
+    TP_EXHAUSTIVE=1 (about 80 s on 8 cores; last full run: 2,237,668,968 inputs, max 1.916 ULP)."""
+    exe = tmp_path / "sweep"
+    subprocess.run(["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-mfma", "-o", str(exe),
+                    os.path.join(ROOT, "tests", "host_extexp_sweep.c"), "-lm", "-lpthread"], check=True)
+    stride = "1" if os.environ.get("TP_EXHAUSTIVE") == "1" else "9"
+    threads = str(min(16, os.cpu_count() or 1))
+    out = subprocess.run([str(exe), "-104", "89", stride, threads, "4"], check=True,
+                         capture_output=True, text=True).stdout.split()
+    count, max_ulp, min_m, max_m, bad_n = int(out[0]), float(out[1]), float(out[2]), float(out[3]), int(out[4])
+    assert count > 2.2e9 / int(stride) * 0.99
+    assert max_ulp < 2.0, out
+    assert bad_n == 0
+    # Section 4: m = e^t with t in [-ln2/2, ln2/2], up to the slop of rounding x log2(e)
+    assert math.sqrt(2) / 2 * (1 - 1e-5) <= min_m and max_m <= math.sqrt(2) * (1 + 1e-5)
+    # beyond the valid range of a plain fp32 exp the pair is still exact to a few ULP
+    out = subprocess.run([str(exe), "-100000", "100000", "4001", threads], check=True,
+                         capture_output=True, text=True).stdout.split()
+    assert int(out[4]) == 0 and 0.70 < float(out[2]) and float(out[3]) < 1.43
