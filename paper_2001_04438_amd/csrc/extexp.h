@@ -32,3 +32,31 @@ TP_FN void tp_extexp(float x, float *m, float *n)
     *m = p;
     *n = nn;
 }
+
+// The same evaluation with the polynomial pre-multiplied by a factor s: cs[0] = s and
+// cs[k] = fl(c_k * s), so the Horner chain ends in s * m instead of m at no extra cost per
+// element.  Pass 2 of Algorithm 3 uses it with s = lambda_sum = 1 / m_sum; the 2^(n - n_sum)
+// factor is applied afterwards.  Costs one rounding per coefficient (about 0.3 ULP in all).
+TP_FN void tp_scale_coeffs(float s, float *cs)
+{
+    cs[0] = s;
+    cs[1] = TP_EXP_C1 * s;
+    cs[2] = TP_EXP_C2 * s;
+    cs[3] = TP_EXP_C3 * s;
+    cs[4] = TP_EXP_C4 * s;
+    cs[5] = TP_EXP_C5 * s;
+}
+
+TP_FN void tp_extexp_scaled(float x, const float *cs, float *ms, float *n)
+{
+    float nn = __builtin_rintf(x * TP_LOG2E);
+    float t = __builtin_fmaf(nn, -TP_LN2_HI, x);
+    t = __builtin_fmaf(nn, -TP_LN2_LO, t);
+    float p = __builtin_fmaf(cs[5], t, cs[4]);
+    p = __builtin_fmaf(p, t, cs[3]);
+    p = __builtin_fmaf(p, t, cs[2]);
+    p = __builtin_fmaf(p, t, cs[1]);
+    p = __builtin_fmaf(p, t, cs[0]);
+    *ms = p;
+    *n = nn;
+}

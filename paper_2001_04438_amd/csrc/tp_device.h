@@ -297,8 +297,10 @@ __device__ __forceinline__ Seg<IO> make_seg(const typename IO::elem *x, typename
         jhi = jlo;
     s.head = a ? (int)(n < (int64_t)(V - a) ? n : (int64_t)(V - a)) : 0;
     s.tail0 = jhi > jlo ? jhi * V - a : (int64_t)s.head;
-    s.xv = (const typename IO::vec *)((uintptr_t)s.xrow - (uintptr_t)a * sizeof(elem));
-    s.yv = (typename IO::vec *)((uintptr_t)s.yrow - (uintptr_t)a * sizeof(elem));
+    // plain pointer arithmetic (no integer round trip) so the compiler keeps treating these
+    // as global-memory pointers and emits global_load / global_store, not flat accesses
+    s.xv = reinterpret_cast<const typename IO::vec *>(s.xrow - a);
+    s.yv = y ? reinterpret_cast<typename IO::vec *>(s.yrow - a) : nullptr;
     int64_t vb = jlo + chunk * chunk_vecs;
     int64_t ve = vb + chunk_vecs;
     if (vb > jhi) vb = jhi;
@@ -434,18 +436,24 @@ struct PairSum {
     }
 };
 
-// Two-Pass, pass 2: Y_i = m_i * lambda * 2^(n_i - n_sum).
+// Two-Pass, pass 2: Y_i = m_i * lambda * 2^(n_i - n_sum).  lambda is folded into the
+// polynomial's coefficients once per thread, so m_i * lambda comes out of the Horner chain.
 struct PairOut {
     static constexpr bool kWrite = true;
-    float lambda, n_sum;
+    float cs[6];
+    float n_sum;
+    __device__ __forceinline__ PairOut(float lambda, float n_sum_) : n_sum(n_sum_)
+    {
+        tp_scale_coeffs(lambda, cs);
+    }
     template <int G>
     __device__ __forceinline__ void group(const float *f, float *o)
     {
 #pragma unroll
         for (int i = 0; i < G; ++i) {
-            float mi, ni;
-            tp_extexp(f[i], &mi, &ni);
-            o[i] = scale_pow2(mi * lambda, ni - n_sum);
+            float ml, ni;
+            tp_extexp_scaled(f[i], cs, &ml, &ni);
+            o[i] = scale_pow2(ml, ni - n_sum);
         }
     }
 };
@@ -479,16 +487,25 @@ struct SumExp {
     }
 };
 
-// Three-Pass (recompute), pass 3: Y_i = lambda * Exp(x - mu).
+// Three-Pass (recompute), pass 3: Y_i = lambda * Exp(x - mu), lambda folded into the
+// polynomial as in PairOut so both families pay the same per element.
 struct ExpScale {
     static constexpr bool kWrite = true;
-    float mu, lambda;
+    float cs[6];
+    float mu;
+    __device__ __forceinline__ ExpScale(float mu_, float lambda) : mu(mu_)
+    {
+        tp_scale_coeffs(lambda, cs);
+    }
     template <int G>
     __device__ __forceinline__ void group(const float *f, float *o)
     {
 #pragma unroll
-        for (int i = 0; i < G; ++i)
-            o[i] = lambda * exp_nonpos(f[i] - mu);
+        for (int i = 0; i < G; ++i) {
+            float ml, ni;
+            tp_extexp_scaled(f[i] - mu, cs, &ml, &ni);
+            o[i] = scale_pow2(ml, ni);
+        }
     }
 };
 

@@ -29,7 +29,7 @@ __global__ __launch_bounds__(BLOCK) void rows_2p(const typename IO::elem *x,
     PairSum acc;
     stream<IO, BLOCK, U, kLoadKeep, kStoreStream>(s, acc);
     block_pair<BLOCK>(acc.m, acc.n, lds);
-    PairOut out{1.0f / acc.m, acc.n};
+    PairOut out(1.0f / acc.m, acc.n);
     stream<IO, BLOCK, U, kLoadStream, kStoreStream>(s, out);
 }
 
@@ -45,7 +45,7 @@ __global__ __launch_bounds__(BLOCK) void rows_3p_recompute(const typename IO::el
     SumExp se{mu};
     stream<IO, BLOCK, U, kLoadKeep, kStoreStream>(s, se);
     const float sigma = block_sum<BLOCK>(se.s, lds);
-    ExpScale es{mu, 1.0f / sigma};
+    ExpScale es(mu, 1.0f / sigma);
     stream<IO, BLOCK, U, kLoadStream, kStoreStream>(s, es);
 }
 
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(BLOCK) void chunk_2p_pass2(const typename IO::elem 
     TP_CHUNK_PROLOGUE
     const float2 q = pairs[row];
     const Seg<IO> s = make_seg<IO>(x, y, a.n, row, chunk, a.chunk_vecs);
-    PairOut out{1.0f / q.x, q.y};
+    PairOut out(1.0f / q.x, q.y);
     stream<IO, BLOCK, U, kLoadStream, kStoreStream>(s, out);
 }
 
@@ -153,7 +153,7 @@ __global__ __launch_bounds__(BLOCK) void chunk_expscale(const typename IO::elem 
 {
     TP_CHUNK_PROLOGUE
     const Seg<IO> s = make_seg<IO>(x, y, a.n, row, chunk, a.chunk_vecs);
-    ExpScale es{rowmax[row], 1.0f / rowsum[row]};
+    ExpScale es(rowmax[row], 1.0f / rowsum[row]);
     stream<IO, BLOCK, U, kLoadStream, kStoreStream>(s, es);
 }
 
