@@ -123,6 +123,8 @@ typedef struct {
                               2: rows cut into chunks, one launch per pass + small merge launches */
     int32_t vector_elems;  /* elements per access: 4 (fp32) / 8 (bf16), or 1 when unaligned */
     int32_t launches;      /* kernel launches of the Two-Pass call */
+    int32_t merge_kernel;  /* path 2: 1 if a row has more than 64 chunk partials, which a small
+                              kernel of its own then merges; 0 if the next pass folds them itself */
     int32_t nt_first_load; /* path 2: 1 if even the first read of x carries the non-temporal hint
                               (input too large for any cache to help the second read) */
     softmax_tp_shape_t rows;    /* path 1 */

@@ -55,6 +55,7 @@ class Plan(ctypes.Structure):
         ("path", ctypes.c_int32),
         ("vector_elems", ctypes.c_int32),
         ("launches", ctypes.c_int32),
+        ("merge_kernel", ctypes.c_int32),
         ("nt_first_load", ctypes.c_int32),
         ("rows", Shape),
         ("reduce", Shape),

@@ -153,7 +153,9 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
             return TP_ERR_TUNING;
     p->nt_first_load = g_tune.nt_first ? (g_tune.nt_first == 2)
                                        : (rows * row_bytes >= kNtFirstBytes);
-    p->launches = 3;  // pass 1, merge, pass 2
+    // up to kFoldMax partials per row are folded by the consuming pass itself
+    p->merge_kernel = p->reduce.chunks > kFoldMax ? 1 : 0;
+    p->launches = 2 + p->merge_kernel;
     const int64_t most = p->reduce.chunks > p->mapsum.chunks ? p->reduce.chunks : p->mapsum.chunks;
     p->workspace_bytes = (2 * rows * most + 2 * rows) * (int64_t)sizeof(float);
     return TP_OK;
@@ -276,7 +278,8 @@ static int run_rows(Algo algo, const softmax_tp_plan_t &plan, const typename IO:
     });
 }
 
-// Two-Pass pass 1 on the chunk path: partial pairs, then one merged pair per row in `merged`.
+// Two-Pass pass 1 on the chunk path: partial pairs; if `merged` is given, one merged pair
+// per row as well.
 template <class IO>
 static int run_2p_pass1(const softmax_tp_plan_t &plan, const typename IO::elem *x, int64_t rows,
                         int64_t n, hipStream_t st, float2 *partial, float2 *merged)
@@ -292,7 +295,7 @@ static int run_2p_pass1(const softmax_tp_plan_t &plan, const typename IO::elem *
             hipLaunchKernelGGL((chunk_2p_pass1<IO, TP_B, TP_U, false>), grid, dim3(TP_B), 0, st, x,
                                a, partial);
     });
-    if (rc != TP_OK)
+    if (rc != TP_OK || !merged)
         return rc;
     hipLaunchKernelGGL(merge_pairs_kernel, dim3((uint32_t)rows), dim3(kMergeBlock), 0, st, partial,
                        (int)plan.reduce.chunks, merged);
@@ -302,13 +305,13 @@ static int run_2p_pass1(const softmax_tp_plan_t &plan, const typename IO::elem *
 template <class IO>
 static int run_2p_pass2(const softmax_tp_plan_t &plan, const typename IO::elem *x,
                         typename IO::elem *y, int64_t rows, int64_t n, hipStream_t st,
-                        const float2 *merged)
+                        const float2 *pairs, int npairs)
 {
     const ChunkArgs a = chunk_args(n, plan.map, rows, pass_reversed(1));
     const dim3 grid = chunk_grid(rows, plan.map);
     return with_shape<IO>(plan.map, [&](auto B, auto U) {
-        hipLaunchKernelGGL((chunk_2p_pass2<IO, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y, a,
-                           merged);
+        hipLaunchKernelGGL((chunk_2p_pass2<IO, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y, a, pairs,
+                           npairs);
     });
 }
 
@@ -321,11 +324,12 @@ static int run_chunks_2p(const softmax_tp_plan_t &plan, const typename IO::elem 
     if (rc != TP_OK)
         return rc;
     float2 *partial = (float2 *)ws;
-    float2 *merged = partial + rows * plan.reduce.chunks;
+    float2 *merged = plan.merge_kernel ? partial + rows * plan.reduce.chunks : nullptr;
     rc = run_2p_pass1<IO>(plan, x, rows, n, st, partial, merged);
     if (rc != TP_OK)
         return rc;
-    return run_2p_pass2<IO>(plan, x, y, rows, n, st, merged);
+    return merged ? run_2p_pass2<IO>(plan, x, y, rows, n, st, merged, 1)
+                  : run_2p_pass2<IO>(plan, x, y, rows, n, st, partial, (int)plan.reduce.chunks);
 }
 
 template <class IO>
@@ -345,6 +349,8 @@ static int run_chunks_3p(Algo algo, const softmax_tp_plan_t &plan, const typenam
     const dim3 merge_grid((uint32_t)rows), merge_block(kMergeBlock);
 
     // pass 1: mu
+    const float *maxes = pmax;
+    int nmax = (int)plan.reduce.chunks;
     {
         const ChunkArgs a = chunk_args(n, plan.reduce, rows, pass_reversed(0));
         rc = with_shape<IO>(plan.reduce, [&](auto B, auto U) {
@@ -357,12 +363,16 @@ static int run_chunks_3p(Algo algo, const softmax_tp_plan_t &plan, const typenam
         });
         if (rc != TP_OK)
             return rc;
-        hipLaunchKernelGGL(merge_max_kernel, merge_grid, merge_block, 0, st, pmax,
-                           (int)plan.reduce.chunks, rowmax);
-        if ((rc = launch_status()) != TP_OK)
-            return rc;
+        if (nmax > kFoldMax) {
+            hipLaunchKernelGGL(merge_max_kernel, merge_grid, merge_block, 0, st, pmax, nmax, rowmax);
+            if ((rc = launch_status()) != TP_OK)
+                return rc;
+            maxes = rowmax;
+            nmax = 1;
+        }
     }
     // pass 2: sigma (and, for the reload variant, y = Exp(x - mu))
+    const float *sums = psum;
     int nsum = 0;
     if (algo == kRecompute) {
         const ChunkArgs a = chunk_args(n, plan.reduce, rows, pass_reversed(1));
@@ -370,10 +380,10 @@ static int run_chunks_3p(Algo algo, const softmax_tp_plan_t &plan, const typenam
         rc = with_shape<IO>(plan.reduce, [&](auto B, auto U) {
             if (nt)
                 hipLaunchKernelGGL((chunk_sumexp<IO, TP_B, TP_U, true>), rgrid, dim3(TP_B), 0, st, x,
-                                   a, rowmax, psum);
+                                   a, maxes, nmax, psum);
             else
                 hipLaunchKernelGGL((chunk_sumexp<IO, TP_B, TP_U, false>), rgrid, dim3(TP_B), 0, st,
-                                   x, a, rowmax, psum);
+                                   x, a, maxes, nmax, psum);
         });
     } else {
         const ChunkArgs a = chunk_args(n, plan.mapsum, rows, pass_reversed(1));
@@ -381,26 +391,30 @@ static int run_chunks_3p(Algo algo, const softmax_tp_plan_t &plan, const typenam
         nsum = (int)plan.mapsum.chunks;
         rc = with_shape<IO>(plan.mapsum, [&](auto B, auto U) {
             hipLaunchKernelGGL((chunk_expstore<IO, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y, a,
-                               rowmax, psum);
+                               maxes, nmax, psum);
         });
     }
     if (rc != TP_OK)
         return rc;
-    hipLaunchKernelGGL(merge_sum_kernel, merge_grid, merge_block, 0, st, psum, nsum, rowsum);
-    if ((rc = launch_status()) != TP_OK)
-        return rc;
+    if (nsum > kFoldMax) {
+        hipLaunchKernelGGL(merge_sum_kernel, merge_grid, merge_block, 0, st, psum, nsum, rowsum);
+        if ((rc = launch_status()) != TP_OK)
+            return rc;
+        sums = rowsum;
+        nsum = 1;
+    }
     // pass 3: y
     const ChunkArgs a = chunk_args(n, plan.map, rows, pass_reversed(2));
     const dim3 grid = chunk_grid(rows, plan.map);
     if (algo == kRecompute)
         return with_shape<IO>(plan.map, [&](auto B, auto U) {
             hipLaunchKernelGGL((chunk_expscale<IO, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y, a,
-                               rowmax, rowsum);
+                               maxes, nmax, sums, nsum);
         });
     const typename IO::elem *yc = y;
     return with_shape<IO>(plan.map, [&](auto B, auto U) {
-        hipLaunchKernelGGL((chunk_scale<IO, TP_B, TP_U>), grid, dim3(TP_B), 0, st, yc, y, a, rowsum,
-                           0.f);
+        hipLaunchKernelGGL((chunk_scale<IO, TP_B, TP_U>), grid, dim3(TP_B), 0, st, yc, y, a, sums,
+                           nsum, 0.f);
     });
 }
 
@@ -535,8 +549,8 @@ int softmax2p_f32_pass2(const float *x, const float *pairs, float *y, int64_t ro
     if ((rc = make_plan(rows, n, 4, vec, 2, &plan)) != TP_OK)
         return rc;
     hipStream_t st = (hipStream_t)stream;
-    return vec ? run_2p_pass2<F32x4>(plan, x, y, rows, n, st, (const float2 *)pairs)
-               : run_2p_pass2<F32x1>(plan, x, y, rows, n, st, (const float2 *)pairs);
+    return vec ? run_2p_pass2<F32x4>(plan, x, y, rows, n, st, (const float2 *)pairs, 1)
+               : run_2p_pass2<F32x1>(plan, x, y, rows, n, st, (const float2 *)pairs, 1);
 }
 
 int softmax_tp_stream_read_f32(const float *x, float *sink, int64_t count, void *stream)
@@ -600,11 +614,11 @@ int softmax_tp_stream_scale_f32(const float *x, float *y, float scale, int64_t c
     if (vec)
         return with_shape<F32x4>(plan.map, [&](auto B, auto U) {
             hipLaunchKernelGGL((chunk_scale<F32x4, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y, a,
-                               none, scale);
+                               none, 0, scale);
         });
     return with_shape<F32x1>(plan.map, [&](auto B, auto U) {
         hipLaunchKernelGGL((chunk_scale<F32x1, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y, a, none,
-                           scale);
+                           0, scale);
     });
 }
 

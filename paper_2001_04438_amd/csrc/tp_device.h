@@ -102,6 +102,36 @@ __device__ __forceinline__ void wave_pair(float &m, float &n)
     n = nw;
 }
 
+// A row's few (<= 64) partial results folded by every wave on its own: lane i takes
+// partial i, then the wave reduction.  No LDS, no barrier, and every wave of every
+// workgroup gets the bit-identical value.
+constexpr int kFoldMax = kWave;
+
+__device__ __forceinline__ void wave_fold_pairs(const float2 *p, int cnt, float &m, float &n)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    m = 0.f;
+    n = kNIdent;
+    if (lane < cnt) {
+        const float2 q = p[lane];
+        m = q.x;
+        n = q.y;
+    }
+    wave_pair(m, n);
+}
+
+__device__ __forceinline__ float wave_fold_max(const float *p, int cnt)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    return wave_max(lane < cnt ? p[lane] : -__builtin_inff());
+}
+
+__device__ __forceinline__ float wave_fold_sum(const float *p, int cnt)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    return wave_sum(lane < cnt ? p[lane] : 0.f);
+}
+
 // ---------------------------------------------------------------------------
 // workgroup-level reductions (result returned to every thread)
 // ---------------------------------------------------------------------------

@@ -3,8 +3,9 @@
 // rows path   rows_*: one workgroup owns a whole row and runs every pass of the
 //             algorithm in one launch; the re-read of the row comes from L2.
 // chunk path  chunk_*: a row is cut into chunks, one workgroup each.  A reducing
-//             pass leaves one partial result per chunk; merge_* folds the partials
-//             of every row into one value that the next pass reads.
+//             pass leaves one partial result per chunk.  The next pass folds up to
+//             64 partials per row itself (one per lane, a wave reduction); beyond
+//             that merge_* folds them into one value per row first.
 #pragma once
 #include "tp_device.h"
 
@@ -105,16 +106,18 @@ __global__ __launch_bounds__(BLOCK) void chunk_2p_pass1(const typename IO::elem 
         partial[wg] = make_float2(acc.m, acc.n);
 }
 
-// Two-Pass pass 2: pairs[row] = (m_sum, n_sum) of the row.
+// Two-Pass pass 2.  pairs holds `npairs` (<= 64) pairs per row: the chunk partials of
+// pass 1, or the single merged pair.
 template <class IO, int BLOCK, int U>
 __global__ __launch_bounds__(BLOCK) void chunk_2p_pass2(const typename IO::elem *x,
                                                         typename IO::elem *y, ChunkArgs a,
-                                                        const float2 *pairs)
+                                                        const float2 *pairs, int npairs)
 {
     TP_CHUNK_PROLOGUE
-    const float2 q = pairs[row];
+    float m_sum, n_sum;
+    wave_fold_pairs(pairs + row * npairs, npairs, m_sum, n_sum);
     const Seg<IO> s = make_seg<IO>(x, y, a.n, row, chunk, a.chunk_vecs);
-    PairOut out(1.0f / q.x, q.y);
+    PairOut out(1.0f / m_sum, n_sum);
     stream<IO, BLOCK, U, kLoadStream, kStoreStream>(s, out);
 }
 
@@ -134,12 +137,12 @@ __global__ __launch_bounds__(BLOCK) void chunk_max(const typename IO::elem *x, C
 
 template <class IO, int BLOCK, int U, bool NT_FIRST>
 __global__ __launch_bounds__(BLOCK) void chunk_sumexp(const typename IO::elem *x, ChunkArgs a,
-                                                      const float *rowmax, float *psum)
+                                                      const float *maxes, int nmax, float *psum)
 {
     __shared__ float lds[2 * kMaxWaves];
     TP_CHUNK_PROLOGUE
     const Seg<IO> s = make_seg<IO>(x, nullptr, a.n, row, chunk, a.chunk_vecs);
-    SumExp se{rowmax[row]};
+    SumExp se{wave_fold_max(maxes + row * nmax, nmax)};
     stream<IO, BLOCK, U, NT_FIRST, kStoreStream>(s, se);
     const float v = block_sum<BLOCK>(se.s, lds);
     if (threadIdx.x == 0)
@@ -149,38 +152,42 @@ __global__ __launch_bounds__(BLOCK) void chunk_sumexp(const typename IO::elem *x
 template <class IO, int BLOCK, int U>
 __global__ __launch_bounds__(BLOCK) void chunk_expscale(const typename IO::elem *x,
                                                         typename IO::elem *y, ChunkArgs a,
-                                                        const float *rowmax, const float *rowsum)
+                                                        const float *maxes, int nmax,
+                                                        const float *sums, int nsum)
 {
     TP_CHUNK_PROLOGUE
+    const float mu = wave_fold_max(maxes + row * nmax, nmax);
+    const float sigma = wave_fold_sum(sums + row * nsum, nsum);
     const Seg<IO> s = make_seg<IO>(x, y, a.n, row, chunk, a.chunk_vecs);
-    ExpScale es(rowmax[row], 1.0f / rowsum[row]);
+    ExpScale es(mu, 1.0f / sigma);
     stream<IO, BLOCK, U, kLoadStream, kStoreStream>(s, es);
 }
 
 template <class IO, int BLOCK, int U>
 __global__ __launch_bounds__(BLOCK) void chunk_expstore(const typename IO::elem *x,
                                                         typename IO::elem *y, ChunkArgs a,
-                                                        const float *rowmax, float *psum)
+                                                        const float *maxes, int nmax, float *psum)
 {
     __shared__ float lds[2 * kMaxWaves];
     TP_CHUNK_PROLOGUE
     const Seg<IO> s = make_seg<IO>(x, y, a.n, row, chunk, a.chunk_vecs);
-    ExpStoreSum ess{rowmax[row]};
+    ExpStoreSum ess{wave_fold_max(maxes + row * nmax, nmax)};
     stream<IO, BLOCK, U, kLoadStream, kStoreKeep>(s, ess);
     const float v = block_sum<BLOCK>(ess.s, lds);
     if (threadIdx.x == 0)
         psum[wg] = v;
 }
 
-// y = x / rowsum[row] (reload pass 3, x == y); with rowsum == nullptr: y = lambda * x.
+// y = x / sigma (reload pass 3, x == y; `nsum` <= 64 partial sums per row);
+// with sums == nullptr: y = lambda * x.
 template <class IO, int BLOCK, int U>
 __global__ __launch_bounds__(BLOCK) void chunk_scale(const typename IO::elem *x,
                                                      typename IO::elem *y, ChunkArgs a,
-                                                     const float *rowsum, float lambda)
+                                                     const float *sums, int nsum, float lambda)
 {
     TP_CHUNK_PROLOGUE
-    if (rowsum)
-        lambda = 1.0f / rowsum[row];
+    if (sums)
+        lambda = 1.0f / wave_fold_sum(sums + row * nsum, nsum);
     const Seg<IO> s = make_seg<IO>(x, y, a.n, row, chunk, a.chunk_vecs);
     Scale sc{lambda};
     stream<IO, BLOCK, U, kLoadStream, kStoreStream>(s, sc);

@@ -72,7 +72,9 @@ CONFIGS = [(1, 4096, 4), (1024, 32768, 4), (64, 1_000_000, 4), (1, 1 << 28, 4), 
 def test_planner_on_the_benchmark_configurations(B):
     plans = [B.softmax_tp_plan(r, n, s) for r, n, s in CONFIGS]
     assert [p.path for p in plans] == [1, 1, 2, 2, 1]
-    assert [p.launches for p in plans] == [1, 1, 3, 3, 1]
+    assert [p.launches for p in plans] == [1, 1, 2, 3, 1]
+    assert plans[2].merge_kernel == 0 and plans[2].reduce.chunks <= 64   # folded by pass 2 itself
+    assert plans[3].merge_kernel == 1 and plans[3].reduce.chunks > 64
     assert plans[1].rows.block == 1024                      # config 2: one workgroup per row
     assert plans[4].vector_elems == 8 and plans[4].rows.unroll <= 4
     assert plans[3].nt_first_load == 1 and plans[2].nt_first_load == 0
