@@ -80,6 +80,22 @@ TP_API int softmax3p_reload_f32(const float *x, float *y, int64_t rows, int64_t 
  */
 TP_API int softmax2p_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n, void *stream);
 
+/*
+ * On-chip variant of Algorithm 3 for short rows (n <= TP_ONCHIP_MAX_N): a workgroup
+ * loads a row into registers, runs pass 1 and pass 2 on the registers and writes y, while
+ * the loads of its next row are already in flight.  Same arithmetic and results as
+ * softmax2p_f32 / softmax2p_bf16io up to summation order, but x is read from memory only
+ * once (2 N elements of traffic instead of 3 N): the regime in which, as the paper notes
+ * (Sections 6.5 and 8), the Two-Pass algorithm has no bandwidth advantage left to offer.
+ * Kept as an entry point of its own so that its throughput is never mistaken for the
+ * three-traversal algorithm's.  x and y must be congruent modulo 16 bytes
+ * (TP_ERR_ALIGN otherwise); longer rows give TP_ERR_TOO_LARGE.
+ */
+#define TP_ONCHIP_MAX_N 32768
+TP_API int softmax2p_onchip_f32(const float *x, float *y, int64_t rows, int64_t n, void *stream);
+TP_API int softmax2p_onchip_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n,
+                                   void *stream);
+
 /* ----- pieces of the path, exported for tests and for per-pass timing ----- */
 
 /*

@@ -23,6 +23,8 @@ ENTRY_POINTS = {
     "softmax3p_recompute_f32": [_vp, _vp, _i64, _i64, _vp],
     "softmax3p_reload_f32": [_vp, _vp, _i64, _i64, _vp],
     "softmax2p_bf16io": [_vp, _vp, _i64, _i64, _vp],
+    "softmax2p_onchip_f32": [_vp, _vp, _i64, _i64, _vp],
+    "softmax2p_onchip_bf16io": [_vp, _vp, _i64, _i64, _vp],
     "softmax_tp_extexp_f32": [_vp, _vp, _vp, _i64, _vp],
     "softmax2p_f32_pass1": [_vp, _vp, _i64, _i64, _vp],
     "softmax2p_f32_pass2": [_vp, _vp, _vp, _i64, _i64, _vp],
@@ -152,6 +154,14 @@ def softmax3p_reload_f32(x, y, rows, n, stream=None):
 
 def softmax2p_bf16io(x, y, rows, n, stream=None):
     _softmax("softmax2p_bf16io", x, y, rows, n, stream)
+
+
+def softmax2p_onchip_f32(x, y, rows, n, stream=None):
+    _softmax("softmax2p_onchip_f32", x, y, rows, n, stream)
+
+
+def softmax2p_onchip_bf16io(x, y, rows, n, stream=None):
+    _softmax("softmax2p_onchip_bf16io", x, y, rows, n, stream)
 
 
 def softmax_tp_extexp_f32(x, m, e, count, stream=None):

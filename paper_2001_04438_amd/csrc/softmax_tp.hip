@@ -440,6 +440,143 @@ static bool congruent16(const void *x, const void *y)
     return (((uintptr_t)x ^ (uintptr_t)y) & 15u) == 0;
 }
 
+// ---- on-chip rows ------------------------------------------------------------------
+
+struct OnchipShape {
+    int block, unroll, mode;
+};
+
+// A row must fit block * unroll vectors.  lo / hi bound the number of whole vectors a row
+// can have (it depends on where the row starts relative to a 16-byte boundary).  Preferred:
+// a tile the rows fill exactly, then tiles whose first unroll - 1 slots every row fills
+// (least padding first), then the catch-all with 1024 threads.
+static bool onchip_shape(int64_t lo, int64_t hi, bool exact, int unroll_max, OnchipShape *out)
+{
+    static const int blocks[] = {1024, 512, 256};
+    bool found = false;
+    int64_t best_pad = 0;
+    for (int b : blocks) {
+        const int64_t u = hi <= b ? 1 : (hi + b - 1) / b;
+        if (u > unroll_max)
+            continue;
+        if (exact && hi == b * u && (u == 1 || u == 2 || u == 4 || u == 8)) {
+            *out = OnchipShape{b, (int)u, kTileFull};
+            return true;
+        }
+        if ((u - 1) * b > lo)
+            continue;
+        const int64_t pad = b * u - hi;
+        if (!found || pad < best_pad) {
+            found = true;
+            best_pad = pad;
+            *out = OnchipShape{b, (int)u, kTileMostly};
+        }
+    }
+    if (found)
+        return true;
+    const int64_t u = (hi + 1023) / 1024;
+    if (u > unroll_max)
+        return false;
+    *out = OnchipShape{1024, (int)(u < 1 ? 1 : u), kTileAny};
+    return true;
+}
+
+// Workgroups of `kernel` that fit on the device at once (cached per device and kernel).
+static int resident_workgroups(const void *kernel, int block, int *out)
+{
+    static std::mutex mu;
+    static std::map<std::pair<int, const void *>, int> cache;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return (int)e;
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = cache.find(std::make_pair(dev, kernel));
+    if (it == cache.end()) {
+        int per_cu = 0, cus = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, block, 0);
+        if (e != hipSuccess)
+            return (int)e;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess)
+            return (int)e;
+        if (per_cu < 1) per_cu = 1;
+        it = cache.emplace(std::make_pair(dev, kernel), per_cu * cus).first;
+    }
+    *out = it->second;
+    return TP_OK;
+}
+
+template <class IO, int B, int U, int MODE>
+static int launch_onchip(const typename IO::elem *x, typename IO::elem *y, int64_t rows, int64_t n,
+                         hipStream_t st)
+{
+    auto kernel = rows_2p_onchip<IO, B, U, MODE>;
+    int resident = 0;
+    int rc = resident_workgroups((const void *)kernel, B, &resident);
+    if (rc != TP_OK)
+        return rc;
+    const int64_t grid = rows < resident ? rows : resident;
+    hipLaunchKernelGGL(kernel, dim3((uint32_t)grid), dim3(B), 0, st, x, y, n, rows);
+    return launch_status();
+}
+
+template <class IO, int B, int U>
+static int launch_onchip_mode(int mode, const typename IO::elem *x, typename IO::elem *y,
+                              int64_t rows, int64_t n, hipStream_t st)
+{
+    if (mode == kTileFull) {
+        if constexpr (U == 1 || U == 2 || U == 4 || U == 8)
+            return launch_onchip<IO, B, U, kTileFull>(x, y, rows, n, st);
+        else
+            return TP_ERR_TUNING;
+    }
+    if (mode == kTileMostly)
+        return launch_onchip<IO, B, U, kTileMostly>(x, y, rows, n, st);
+    if constexpr (B == 1024)
+        return launch_onchip<IO, B, U, kTileAny>(x, y, rows, n, st);
+    else
+        return TP_ERR_TUNING;
+}
+
+template <class IO>
+static int run_onchip(const typename IO::elem *x, typename IO::elem *y, int64_t rows, int64_t n,
+                      void *stream)
+{
+    constexpr int es = (int)sizeof(typename IO::elem);
+    constexpr int V = IO::V;
+    constexpr int umax = es == 4 ? 8 : 4;
+    int rc = check_args(x, y, rows, n, es);
+    if (rc != TP_OK || rows == 0 || n == 0)
+        return rc;
+    if (!congruent16(x, y))
+        return TP_ERR_ALIGN;
+    const bool exact = ((uintptr_t)x % 16) == 0 && n % V == 0;
+    const int64_t hi = (n + V - 1) / V;
+    const int64_t lo = exact ? n / V : (n / V > 0 ? n / V - 1 : 0);
+    OnchipShape sh;
+    if (!onchip_shape(lo, hi, exact, umax, &sh))
+        return TP_ERR_TOO_LARGE;
+    hipStream_t st = (hipStream_t)stream;
+#define TP_OC(B, UU)                                                              \
+    case B * 16 + UU:                                                             \
+        if constexpr (UU <= umax)                                                 \
+            return launch_onchip_mode<IO, B, UU>(sh.mode, x, y, rows, n, st);     \
+        else                                                                      \
+            return TP_ERR_TUNING;
+#define TP_OC_BLOCK(B) \
+    TP_OC(B, 1) TP_OC(B, 2) TP_OC(B, 3) TP_OC(B, 4) TP_OC(B, 5) TP_OC(B, 6) TP_OC(B, 7) TP_OC(B, 8)
+    switch (sh.block * 16 + sh.unroll) {
+        TP_OC_BLOCK(256)
+        TP_OC_BLOCK(512)
+        TP_OC_BLOCK(1024)
+    default:
+        return TP_ERR_TUNING;
+    }
+#undef TP_OC_BLOCK
+#undef TP_OC
+}
+
 template <class IOV, class IOS>
 static int softmax_any(Algo algo, const typename IOV::elem *x, typename IOV::elem *y,
                        int64_t rows, int64_t n, void *stream)
@@ -494,6 +631,16 @@ int softmax3p_reload_f32(const float *x, float *y, int64_t rows, int64_t n, void
 int softmax2p_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n, void *stream)
 {
     return softmax_any<BF16x8, BF16x1>(kTwoPass, x, y, rows, n, stream);
+}
+
+int softmax2p_onchip_f32(const float *x, float *y, int64_t rows, int64_t n, void *stream)
+{
+    return run_onchip<F32x4>(x, y, rows, n, stream);
+}
+
+int softmax2p_onchip_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n, void *stream)
+{
+    return run_onchip<BF16x8>(x, y, rows, n, stream);
 }
 
 int softmax_tp_extexp_f32(const float *x, float *m, float *e, int64_t count, void *stream)

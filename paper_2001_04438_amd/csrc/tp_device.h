@@ -136,6 +136,10 @@ __device__ __forceinline__ float wave_fold_sum(const float *p, int cnt)
 // workgroup-level reductions (result returned to every thread)
 // ---------------------------------------------------------------------------
 
+// Stage 1: wave reduction; stage 2: lane w of every wave picks up wave w's result from
+// LDS and the wave reduces again, so all waves end up with the same bits and only a
+// couple of registers are live across the barrier.
+
 template <int BLOCK>
 __device__ __forceinline__ float block_max(float v, float *lds)
 {
@@ -147,11 +151,8 @@ __device__ __forceinline__ float block_max(float v, float *lds)
     if ((threadIdx.x & (kWave - 1)) == 0)
         lds[threadIdx.x / kWave] = v;
     __syncthreads();
-    float r = lds[0];
-#pragma unroll
-    for (int w = 1; w < W; ++w)
-        r = fmaxf(r, lds[w]);
-    return r;
+    const int lane = threadIdx.x & (kWave - 1);
+    return wave_max(lane < W ? lds[lane] : -__builtin_inff());
 }
 
 template <int BLOCK>
@@ -165,11 +166,8 @@ __device__ __forceinline__ float block_sum(float v, float *lds)
     if ((threadIdx.x & (kWave - 1)) == 0)
         lds[threadIdx.x / kWave] = v;
     __syncthreads();
-    float r = lds[0];
-#pragma unroll
-    for (int w = 1; w < W; ++w)
-        r += lds[w];
-    return r;
+    const int lane = threadIdx.x & (kWave - 1);
+    return wave_sum(lane < W ? lds[lane] : 0.f);
 }
 
 template <int BLOCK>
@@ -185,16 +183,10 @@ __device__ __forceinline__ void block_pair(float &m, float &n, float *lds)
         lds[kMaxWaves + threadIdx.x / kWave] = n;
     }
     __syncthreads();
-    float nb = lds[kMaxWaves];
-#pragma unroll
-    for (int w = 1; w < W; ++w)
-        nb = fmaxf(nb, lds[kMaxWaves + w]);
-    float mb = scale_pow2(lds[0], lds[kMaxWaves] - nb);
-#pragma unroll
-    for (int w = 1; w < W; ++w)
-        mb += scale_pow2(lds[w], lds[kMaxWaves + w] - nb);
-    m = mb;
-    n = nb;
+    const int lane = threadIdx.x & (kWave - 1);
+    m = lane < W ? lds[lane] : 0.f;
+    n = lane < W ? lds[kMaxWaves + lane] : kNIdent;
+    wave_pair(m, n);
 }
 
 // ---------------------------------------------------------------------------

@@ -68,6 +68,172 @@ __global__ __launch_bounds__(BLOCK) void rows_3p_reload(const typename IO::elem 
     stream<IO, BLOCK, U, kLoadStream, kStoreStream>(sy, sc);
 }
 
+// ---- on-chip rows: the row stays in registers between the passes -------------------
+//
+// For rows of at most BLOCK * U vectors.  A workgroup walks rows blockIdx.x,
+// blockIdx.x + gridDim.x, ...; the loads of its next row are issued before it starts
+// computing on the current one, so memory and ALU work overlap inside one workgroup.
+// x is read from memory once and y written once (2 N s bytes): the second read of
+// Algorithm 3 is served by the register file.  Reported as a variant of its own.
+
+template <class IO, int U>
+struct RowRegs {
+    typename IO::vec v[U];
+    float edge;
+};
+
+template <class IO>
+__device__ __forceinline__ int64_t edge_index(const Seg<IO> &s)
+{
+    return (int)threadIdx.x < s.head ? (int64_t)threadIdx.x
+                                     : s.tail0 + ((int64_t)threadIdx.x - s.head);
+}
+
+template <class IO>
+__device__ __forceinline__ bool has_edge(const Seg<IO> &s)
+{
+    return (int64_t)threadIdx.x < s.head + (s.n - s.tail0);
+}
+
+// MODE says how much of the tile every row is known to fill:
+//   kTileFull    every thread owns U real vectors and rows have no edge elements,
+//   kTileMostly  the first U - 1 vector slots are full, the last one and the edges are not,
+//   kTileAny     nothing is known.
+// Slots known to be full are loaded and stored without a condition, which matters: see
+// the comment on rows_2p_onchip.
+enum { kTileAny = 0, kTileMostly = 1, kTileFull = 2 };
+
+template <int U, int MODE>
+constexpr int lead_slots()
+{
+    return MODE == kTileFull ? U : MODE == kTileMostly ? U - 1 : 0;
+}
+
+template <class IO, int BLOCK, int U, int MODE>
+__device__ __forceinline__ void load_row(const Seg<IO> &s, RowRegs<IO, U> &r)
+{
+    constexpr int LEAD = lead_slots<U, MODE>();
+    const typename IO::vec *xb = s.xv + s.vb;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t k = threadIdx.x + (uint32_t)(u * BLOCK);
+        if (u < LEAD)
+            r.v[u] = ld<kLoadStream>(xb + k);
+        else
+            r.v[u] = k < s.cnt ? ld<kLoadStream>(xb + k) : IO::zero();
+    }
+    r.edge = 0.f;
+    if (MODE != kTileFull && has_edge(s))
+        r.edge = IO::load1(s.xrow + edge_index(s));
+}
+
+// Feeds vectors [U0, U0 + GV) of the row to the policy: all at once if this thread owns
+// all of them, else one by one.
+template <class IO, int BLOCK, int U, int MODE, int U0, int GV, class P>
+__device__ __forceinline__ void feed_group(const RowRegs<IO, U> &r, uint32_t cnt, P &p)
+{
+    constexpr int V = IO::V;
+    constexpr int LEAD = lead_slots<U, MODE>();
+    if (U0 + GV <= LEAD || threadIdx.x + (uint32_t)((U0 + GV - 1) * BLOCK) < cnt) {
+        float f[GV * V];
+#pragma unroll
+        for (int g = 0; g < GV; ++g)
+            IO::unpack(r.v[U0 + g], f + g * V);
+        p.template group<GV * V>(f, nullptr);
+    } else {
+#pragma unroll
+        for (int g = 0; g < GV; ++g) {
+            if (U0 + g < LEAD || threadIdx.x + (uint32_t)((U0 + g) * BLOCK) < cnt) {
+                float f[V];
+                IO::unpack(r.v[U0 + g], f);
+                p.template group<V>(f, nullptr);
+            }
+        }
+    }
+}
+
+template <class IO, int BLOCK, int U, int MODE, int U0, class P>
+__device__ __forceinline__ void feed_row(const RowRegs<IO, U> &r, uint32_t cnt, P &p)
+{
+    // 16 elements per group; 8 when the row buffers alone take half of the register file
+    constexpr int GVMAX = (U * IO::V >= 32 ? 8 : 16) / IO::V;
+    if constexpr (U0 < U) {
+        constexpr int GV = (U - U0) < GVMAX ? (U - U0) : GVMAX;
+        feed_group<IO, BLOCK, U, MODE, U0, GV>(r, cnt, p);
+        feed_row<IO, BLOCK, U, MODE, U0 + GV>(r, cnt, p);
+    }
+}
+
+// One row from registers: pass 1, workgroup reduction, pass 2, stores.
+template <class IO, int BLOCK, int U, int MODE>
+__device__ __forceinline__ void onchip_row(const Seg<IO> &s, const RowRegs<IO, U> &cur, float *lds)
+{
+    constexpr int V = IO::V;
+    constexpr int LEAD = lead_slots<U, MODE>();
+    PairSum acc;
+    feed_row<IO, BLOCK, U, MODE, 0>(cur, s.cnt, acc);
+    if (MODE != kTileFull && has_edge(s))
+        acc.template group<1>(&cur.edge, nullptr);
+    block_pair<BLOCK>(acc.m, acc.n, lds);
+    PairOut out(1.0f / acc.m, acc.n);
+    typename IO::vec *yb = s.yv + s.vb;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t k = threadIdx.x + (uint32_t)(u * BLOCK);
+        if (u < LEAD || k < s.cnt) {
+            float f[V], o[V];
+            IO::unpack(cur.v[u], f);
+            out.template group<V>(f, o);
+            st<kStoreStream>(yb + k, IO::pack(o));
+        }
+    }
+    if (MODE != kTileFull && has_edge(s)) {
+        float o;
+        out.template group<1>(&cur.edge, &o);
+        IO::store1(s.yrow + edge_index(s), o);
+    }
+}
+
+// Marks the point where a row's registers are needed: the compiler places its wait for
+// the loads here.
+template <class IO, int U>
+__device__ __forceinline__ void touch(RowRegs<IO, U> &r)
+{
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        asm volatile("" : "+v"(r.v[u]));
+}
+
+// Loads and stores share one in-order completion counter on this hardware.  The loads of
+// the next row are issued before the current row is computed and stored, and they are
+// waited for at the bottom of the loop, where the only younger operations are this row's
+// stores: the wait can then leave the stores in flight (as many of them as are issued
+// unconditionally), and they drain while the next row is being computed.  The last row is
+// peeled off so that no load in the loop depends on there being a next row.
+template <class IO, int BLOCK, int U, int MODE>
+__global__ __launch_bounds__(BLOCK) void rows_2p_onchip(const typename IO::elem *x,
+                                                        typename IO::elem *y, int64_t n,
+                                                        int64_t rows)
+{
+    __shared__ float lds[2 * kMaxWaves];
+    int64_t row = blockIdx.x;  // the grid never exceeds the number of rows
+    Seg<IO> s = make_seg<IO>(x, y, n, row, 0, INT64_MAX / 2);
+    RowRegs<IO, U> cur;
+    load_row<IO, BLOCK, U, MODE>(s, cur);
+    touch<IO, U>(cur);
+    for (int64_t row_after = row + gridDim.x; row_after < rows; row_after += gridDim.x) {
+        const Seg<IO> s_next = make_seg<IO>(x, y, n, row_after, 0, INT64_MAX / 2);
+        RowRegs<IO, U> next;
+        load_row<IO, BLOCK, U, MODE>(s_next, next);  // in flight during the current row
+        __builtin_amdgcn_sched_barrier(0);           // keep the loads ahead of the arithmetic
+        onchip_row<IO, BLOCK, U, MODE>(s, cur, lds);
+        touch<IO, U>(next);
+        s = s_next;
+        cur = next;
+    }
+    onchip_row<IO, BLOCK, U, MODE>(s, cur, lds);
+}
+
 // ---- chunk path: grid = rows * chunks, rounded up to a multiple of kXcds ---------
 
 struct ChunkArgs {

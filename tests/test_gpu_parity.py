@@ -214,6 +214,58 @@ def test_nan_poisons_only_its_row(gpu):
 
 
 # ---------------------------------------------------------------------------
+# on-chip variant (row kept in registers between the passes)
+# ---------------------------------------------------------------------------
+
+def test_onchip_f32(gpu, oracle_mod):
+    rng = np.random.default_rng(90)
+    cases = [workloads.cfg1(), workloads.cfg1(probes=True), workloads.cfg2(rows=37, n=32768),
+             workloads.cfg2(rows=700, n=8192),          # more rows than resident workgroups
+             workloads.cfg2(rows=2100, n=1000)]
+    for n in EDGE_N + [8191, 8193, 20000, 28001, 32767]:
+        cases.append(rng.normal(0, 6, size=(3, n)).astype(np.float32))
+    for x in cases:
+        _check(oracle_mod, x, _run(gpu.softmax2p_onchip_f32, x), TOL_2P)
+    x = workloads.cfg2(rows=9, n=5003)
+    for off in (1, 2, 3):                                # rows start anywhere relative to 16 bytes
+        _check(oracle_mod, x, _run(gpu.softmax2p_onchip_f32, x, x_off=off, y_off=off), TOL_2P)
+    _check(oracle_mod, x, _run(gpu.softmax2p_onchip_f32, x, inplace=True), TOL_2P)
+    # same arithmetic as the three-traversal entry point: equal up to summation order
+    x = workloads.cfg2(rows=40, n=32768)
+    a, b = _run(gpu.softmax2p_onchip_f32, x), _run(gpu.softmax2p_f32, x)
+    nz = b > 1e-30
+    assert np.max(np.abs(a[nz] - b[nz]) / b[nz]) < 1e-6
+
+
+def test_onchip_bf16(gpu, oracle_mod):
+    rng = np.random.default_rng(91)
+    cases = [workloads.cfg5(rows=61, n=21846), workloads.cfg5(rows=1500, n=3000),
+             workloads.cfg5(rows=5, n=32768)]
+    for n in EDGE_N + [16383, 21841, 32767]:
+        cases.append(workloads.f32_to_bf16_bits(rng.normal(0, 6, size=(3, n)).astype(np.float32)).reshape(3, n))
+    for x in cases:
+        _check(oracle_mod, x, _run(gpu.softmax2p_onchip_bf16io, x), TOL_BF16, bf16=True)
+    x = workloads.cfg5(rows=7, n=3001)
+    for off in (1, 5, 7):
+        _check(oracle_mod, x, _run(gpu.softmax2p_onchip_bf16io, x, x_off=off, y_off=off), TOL_BF16, bf16=True)
+    _check(oracle_mod, x, _run(gpu.softmax2p_onchip_bf16io, x, inplace=True), TOL_BF16, bf16=True)
+
+
+def test_onchip_limits(gpu):
+    import torch
+    t = torch.zeros(40000, dtype=torch.float32, device="cuda")
+    with pytest.raises(gpu.SoftmaxTpError) as e:            # row longer than the register tile
+        gpu.softmax2p_onchip_f32(t, t, 1, 32769)
+    assert e.value.code == gpu.TP_ERR_TOO_LARGE
+    with pytest.raises(gpu.SoftmaxTpError) as e:            # x and y not congruent modulo 16 bytes
+        gpu.softmax2p_onchip_f32(t, t.data_ptr() + 4, 1, 100)
+    assert e.value.code == gpu.TP_ERR_ALIGN
+    gpu.softmax2p_onchip_f32(t, t, 0, 100)
+    torch.cuda.synchronize()
+    assert float(t.abs().sum()) == 0.0
+
+
+# ---------------------------------------------------------------------------
 # wide dynamic range: nothing overflows, shift invariance
 # ---------------------------------------------------------------------------
 
