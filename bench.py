@@ -103,7 +103,10 @@ def run_workload(torch, B, W, name, steps, warmup, full):
            "plan": plan.as_dict(), "variants": {}}
 
     variants = [("softmax2p", B.softmax2p_bf16io if bf16 else B.softmax2p_f32)]
-    if not bf16:
+    if bf16:
+        variants += [("softmax3p_recompute", B.softmax3p_recompute_bf16io),
+                     ("softmax3p_reload", B.softmax3p_reload_bf16io)]
+    else:
         variants += [("softmax3p_recompute", B.softmax3p_recompute_f32),
                      ("softmax3p_reload", B.softmax3p_reload_f32)]
     if n <= 32768:  # short rows: also the variant that keeps the row in registers

@@ -81,6 +81,17 @@ TP_API int softmax3p_reload_f32(const float *x, float *y, int64_t rows, int64_t 
 TP_API int softmax2p_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n, void *stream);
 
 /*
+ * Algorithms 1 and 2 with bfloat16 storage, as baselines for softmax2p_bf16io: same
+ * widening / rounding as there.  In the reloading variant y holds Exp(x - mu) rounded to
+ * bf16 between the second and the third pass (sigma is accumulated from the unrounded
+ * fp32 values), so its result carries two bf16 roundings.
+ */
+TP_API int softmax3p_recompute_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n,
+                                      void *stream);
+TP_API int softmax3p_reload_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n,
+                                   void *stream);
+
+/*
  * On-chip variant of Algorithm 3 for short rows (n <= TP_ONCHIP_MAX_N): a workgroup
  * loads a row into registers, runs pass 1 and pass 2 on the registers and writes y, while
  * the loads of its next row are already in flight.  Same arithmetic and results as

@@ -23,6 +23,8 @@ ENTRY_POINTS = {
     "softmax3p_recompute_f32": [_vp, _vp, _i64, _i64, _vp],
     "softmax3p_reload_f32": [_vp, _vp, _i64, _i64, _vp],
     "softmax2p_bf16io": [_vp, _vp, _i64, _i64, _vp],
+    "softmax3p_recompute_bf16io": [_vp, _vp, _i64, _i64, _vp],
+    "softmax3p_reload_bf16io": [_vp, _vp, _i64, _i64, _vp],
     "softmax2p_onchip_f32": [_vp, _vp, _i64, _i64, _vp],
     "softmax2p_onchip_bf16io": [_vp, _vp, _i64, _i64, _vp],
     "softmax_tp_extexp_f32": [_vp, _vp, _vp, _i64, _vp],
@@ -154,6 +156,14 @@ def softmax3p_reload_f32(x, y, rows, n, stream=None):
 
 def softmax2p_bf16io(x, y, rows, n, stream=None):
     _softmax("softmax2p_bf16io", x, y, rows, n, stream)
+
+
+def softmax3p_recompute_bf16io(x, y, rows, n, stream=None):
+    _softmax("softmax3p_recompute_bf16io", x, y, rows, n, stream)
+
+
+def softmax3p_reload_bf16io(x, y, rows, n, stream=None):
+    _softmax("softmax3p_reload_bf16io", x, y, rows, n, stream)
 
 
 def softmax2p_onchip_f32(x, y, rows, n, stream=None):

@@ -263,18 +263,13 @@ static int run_rows(Algo algo, const softmax_tp_plan_t &plan, const typename IO:
 {
     const dim3 grid((uint32_t)rows);
     return with_shape<IO>(plan.rows, [&](auto B, auto U) {
-        if constexpr (sizeof(typename IO::elem) == 2) {  // bf16: Two-Pass only
+        if (algo == kTwoPass)
             hipLaunchKernelGGL((rows_2p<IO, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y, n);
-        } else {
-            if (algo == kTwoPass)
-                hipLaunchKernelGGL((rows_2p<IO, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y, n);
-            else if (algo == kRecompute)
-                hipLaunchKernelGGL((rows_3p_recompute<IO, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x,
-                                   y, n);
-            else
-                hipLaunchKernelGGL((rows_3p_reload<IO, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y,
-                                   n);
-        }
+        else if (algo == kRecompute)
+            hipLaunchKernelGGL((rows_3p_recompute<IO, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y,
+                               n);
+        else
+            hipLaunchKernelGGL((rows_3p_reload<IO, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y, n);
     });
 }
 
@@ -597,10 +592,8 @@ static int softmax_any(Algo algo, const typename IOV::elem *x, typename IOV::ele
     if (algo == kTwoPass)
         return vec ? run_chunks_2p<IOV>(plan, x, y, rows, n, st)
                    : run_chunks_2p<IOS>(plan, x, y, rows, n, st);
-    if constexpr (es == 4)
-        return vec ? run_chunks_3p<IOV>(algo, plan, x, y, rows, n, st)
-                   : run_chunks_3p<IOS>(algo, plan, x, y, rows, n, st);
-    return TP_ERR_TUNING;
+    return vec ? run_chunks_3p<IOV>(algo, plan, x, y, rows, n, st)
+               : run_chunks_3p<IOS>(algo, plan, x, y, rows, n, st);
 }
 
 }  // namespace tp
@@ -631,6 +624,17 @@ int softmax3p_reload_f32(const float *x, float *y, int64_t rows, int64_t n, void
 int softmax2p_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n, void *stream)
 {
     return softmax_any<BF16x8, BF16x1>(kTwoPass, x, y, rows, n, stream);
+}
+
+int softmax3p_recompute_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n,
+                               void *stream)
+{
+    return softmax_any<BF16x8, BF16x1>(kRecompute, x, y, rows, n, stream);
+}
+
+int softmax3p_reload_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n, void *stream)
+{
+    return softmax_any<BF16x8, BF16x1>(kReload, x, y, rows, n, stream);
 }
 
 int softmax2p_onchip_f32(const float *x, float *y, int64_t rows, int64_t n, void *stream)

@@ -128,6 +128,17 @@ def test_bf16_chunk_path(gpu, oracle_mod):
     _check(oracle_mod, x, _run(gpu.softmax2p_bf16io, x), TOL_BF16, bf16=True)
 
 
+@pytest.mark.parametrize("name", ["softmax3p_recompute_bf16io", "softmax3p_reload_bf16io"])
+def test_three_pass_bf16_baselines(gpu, oracle_mod, name):
+    for x in (workloads.cfg5(rows=61, n=21846), workloads.cfg5(rows=2, n=300_001),
+              workloads.cfg5(rows=3, n=1003)):
+        _check(oracle_mod, x, _run(getattr(gpu, name), x), TOL_BF16, bf16=True)
+    x = workloads.cfg5(rows=5, n=4001)
+    _check(oracle_mod, x, _run(getattr(gpu, name), x, x_off=3, y_off=3), TOL_BF16, bf16=True)
+    _check(oracle_mod, x, _run(getattr(gpu, name), x, x_off=1, y_off=2), TOL_BF16, bf16=True)
+    _check(oracle_mod, x, _run(getattr(gpu, name), x, inplace=True), TOL_BF16, bf16=True)
+
+
 # ---------------------------------------------------------------------------
 # edge shapes, alignment, aliasing
 # ---------------------------------------------------------------------------
