@@ -31,7 +31,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # algorithmic bytes per element in units of the element size (Table 2); the on-chip variant
 # reads x from memory once and is therefore counted with 2, not 3
-BYTES_PER_ELEM = {"softmax2p": 3, "softmax3p_recompute": 4, "softmax3p_reload": 5, "softmax2p_onchip": 2}
+BYTES_PER_ELEM = {"softmax2p": 3, "softmax3p_recompute": 4, "softmax3p_reload": 5,
+                  "softmax2p_onchip": 2, "softmax3p_onchip": 2}
 
 
 def log(*a):
@@ -110,7 +111,8 @@ def run_workload(torch, B, W, name, steps, warmup, full):
         variants += [("softmax3p_recompute", B.softmax3p_recompute_f32),
                      ("softmax3p_reload", B.softmax3p_reload_f32)]
     if n <= 32768:  # short rows: also the variant that keeps the row in registers
-        variants += [("softmax2p_onchip", B.softmax2p_onchip_bf16io if bf16 else B.softmax2p_onchip_f32)]
+        variants += [("softmax2p_onchip", B.softmax2p_onchip_bf16io if bf16 else B.softmax2p_onchip_f32),
+                     ("softmax3p_onchip", B.softmax3p_onchip_bf16io if bf16 else B.softmax3p_onchip_f32)]
     for vname, fn in variants:
         call = lambda i, fn=fn: fn(xs[i], ys[i], rows, n)
         wall_ms, ev_ms = time_calls(torch, call, steps, warmup, sets)

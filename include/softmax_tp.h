@@ -97,7 +97,7 @@ TP_API int softmax3p_reload_bf16io(const uint16_t *x, uint16_t *y, int64_t rows,
  * the loads of its next row are already in flight.  Same arithmetic and results as
  * softmax2p_f32 / softmax2p_bf16io up to summation order, but x is read from memory only
  * once (2 N elements of traffic instead of 3 N): the regime in which, as the paper notes
- * (Sections 6.5 and 8), the Two-Pass algorithm has no bandwidth advantage left to offer.
+ * (Sections 6.4 and 7), the Two-Pass algorithm has no bandwidth advantage left to offer.
  * Kept as an entry point of its own so that its throughput is never mistaken for the
  * three-traversal algorithm's.  x and y must be congruent modulo 16 bytes
  * (TP_ERR_ALIGN otherwise); longer rows give TP_ERR_TOO_LARGE.
@@ -105,6 +105,17 @@ TP_API int softmax3p_reload_bf16io(const uint16_t *x, uint16_t *y, int64_t rows,
 #define TP_ONCHIP_MAX_N 32768
 TP_API int softmax2p_onchip_f32(const float *x, float *y, int64_t rows, int64_t n, void *stream);
 TP_API int softmax2p_onchip_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n,
+                                   void *stream);
+
+/*
+ * The same on-chip arrangement for Algorithm 2 (Section 3): max, Exp(x - mu) held in
+ * registers where the algorithm holds it in Y, sum, rescale, store.  One exponential per
+ * element, so this is the cheapest of all variants when rows fit on chip: the paper's
+ * finding for in-cache data (Section 6.4), kept here as the honest baseline of
+ * softmax2p_onchip_*.  Same limits and error codes.
+ */
+TP_API int softmax3p_onchip_f32(const float *x, float *y, int64_t rows, int64_t n, void *stream);
+TP_API int softmax3p_onchip_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n,
                                    void *stream);
 
 /* ----- pieces of the path, exported for tests and for per-pass timing ----- */

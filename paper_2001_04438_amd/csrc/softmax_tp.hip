@@ -503,10 +503,11 @@ static int resident_workgroups(const void *kernel, int block, int *out)
 }
 
 template <class IO, int B, int U, int MODE>
-static int launch_onchip(const typename IO::elem *x, typename IO::elem *y, int64_t rows, int64_t n,
-                         hipStream_t st)
+static int launch_onchip(int algo, const typename IO::elem *x, typename IO::elem *y, int64_t rows,
+                         int64_t n, hipStream_t st)
 {
-    auto kernel = rows_2p_onchip<IO, B, U, MODE>;
+    auto kernel = algo == kOnchipTwoPass ? rows_onchip<IO, B, U, MODE, kOnchipTwoPass>
+                                         : rows_onchip<IO, B, U, MODE, kOnchipThreePass>;
     int resident = 0;
     int rc = resident_workgroups((const void *)kernel, B, &resident);
     if (rc != TP_OK)
@@ -517,26 +518,26 @@ static int launch_onchip(const typename IO::elem *x, typename IO::elem *y, int64
 }
 
 template <class IO, int B, int U>
-static int launch_onchip_mode(int mode, const typename IO::elem *x, typename IO::elem *y,
-                              int64_t rows, int64_t n, hipStream_t st)
+static int launch_onchip_mode(int mode, int algo, const typename IO::elem *x,
+                              typename IO::elem *y, int64_t rows, int64_t n, hipStream_t st)
 {
     if (mode == kTileFull) {
         if constexpr (U == 1 || U == 2 || U == 4 || U == 8)
-            return launch_onchip<IO, B, U, kTileFull>(x, y, rows, n, st);
+            return launch_onchip<IO, B, U, kTileFull>(algo, x, y, rows, n, st);
         else
             return TP_ERR_TUNING;
     }
     if (mode == kTileMostly)
-        return launch_onchip<IO, B, U, kTileMostly>(x, y, rows, n, st);
+        return launch_onchip<IO, B, U, kTileMostly>(algo, x, y, rows, n, st);
     if constexpr (B == 1024)
-        return launch_onchip<IO, B, U, kTileAny>(x, y, rows, n, st);
+        return launch_onchip<IO, B, U, kTileAny>(algo, x, y, rows, n, st);
     else
         return TP_ERR_TUNING;
 }
 
 template <class IO>
-static int run_onchip(const typename IO::elem *x, typename IO::elem *y, int64_t rows, int64_t n,
-                      void *stream)
+static int run_onchip(int algo, const typename IO::elem *x, typename IO::elem *y, int64_t rows,
+                      int64_t n, void *stream)
 {
     constexpr int es = (int)sizeof(typename IO::elem);
     constexpr int V = IO::V;
@@ -556,7 +557,7 @@ static int run_onchip(const typename IO::elem *x, typename IO::elem *y, int64_t 
 #define TP_OC(B, UU)                                                              \
     case B * 16 + UU:                                                             \
         if constexpr (UU <= umax)                                                 \
-            return launch_onchip_mode<IO, B, UU>(sh.mode, x, y, rows, n, st);     \
+            return launch_onchip_mode<IO, B, UU>(sh.mode, algo, x, y, rows, n, st); \
         else                                                                      \
             return TP_ERR_TUNING;
 #define TP_OC_BLOCK(B) \
@@ -639,12 +640,22 @@ int softmax3p_reload_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_
 
 int softmax2p_onchip_f32(const float *x, float *y, int64_t rows, int64_t n, void *stream)
 {
-    return run_onchip<F32x4>(x, y, rows, n, stream);
+    return run_onchip<F32x4>(kOnchipTwoPass, x, y, rows, n, stream);
 }
 
 int softmax2p_onchip_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n, void *stream)
 {
-    return run_onchip<BF16x8>(x, y, rows, n, stream);
+    return run_onchip<BF16x8>(kOnchipTwoPass, x, y, rows, n, stream);
+}
+
+int softmax3p_onchip_f32(const float *x, float *y, int64_t rows, int64_t n, void *stream)
+{
+    return run_onchip<F32x4>(kOnchipThreePass, x, y, rows, n, stream);
+}
+
+int softmax3p_onchip_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n, void *stream)
+{
+    return run_onchip<BF16x8>(kOnchipThreePass, x, y, rows, n, stream);
 }
 
 int softmax_tp_extexp_f32(const float *x, float *m, float *e, int64_t count, void *stream)

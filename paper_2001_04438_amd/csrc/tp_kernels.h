@@ -100,7 +100,7 @@ __device__ __forceinline__ bool has_edge(const Seg<IO> &s)
 //   kTileMostly  the first U - 1 vector slots are full, the last one and the edges are not,
 //   kTileAny     nothing is known.
 // Slots known to be full are loaded and stored without a condition, which matters: see
-// the comment on rows_2p_onchip.
+// the comment on rows_onchip.
 enum { kTileAny = 0, kTileMostly = 1, kTileFull = 2 };
 
 template <int U, int MODE>
@@ -164,9 +164,10 @@ __device__ __forceinline__ void feed_row(const RowRegs<IO, U> &r, uint32_t cnt, 
     }
 }
 
-// One row from registers: pass 1, workgroup reduction, pass 2, stores.
+// Algorithm 3 on one row held in registers: pass 1, workgroup reduction, pass 2, stores.
 template <class IO, int BLOCK, int U, int MODE>
-__device__ __forceinline__ void onchip_row(const Seg<IO> &s, const RowRegs<IO, U> &cur, float *lds)
+__device__ __forceinline__ void onchip_row_2p(const Seg<IO> &s, const RowRegs<IO, U> &cur,
+                                              float *lds)
 {
     constexpr int V = IO::V;
     constexpr int LEAD = lead_slots<U, MODE>();
@@ -194,6 +195,68 @@ __device__ __forceinline__ void onchip_row(const Seg<IO> &s, const RowRegs<IO, U
     }
 }
 
+// Algorithm 2 on one row held in registers: max, then Exp(x - mu) kept in registers where
+// the algorithm keeps it in Y, their sum, and the rescaled values stored.  One exponential
+// per element: in this regime the reloading Three-Pass algorithm is the cheapest, as the
+// paper finds for data that fits in cache (Section 6.4).
+template <class IO, int BLOCK, int U, int MODE>
+__device__ __forceinline__ void onchip_row_3p(const Seg<IO> &s, const RowRegs<IO, U> &cur,
+                                              float *lds)
+{
+    constexpr int V = IO::V;
+    constexpr int LEAD = lead_slots<U, MODE>();
+    const bool edge = MODE != kTileFull && has_edge(s);
+    MaxOf mx;
+    feed_row<IO, BLOCK, U, MODE, 0>(cur, s.cnt, mx);
+    if (edge)
+        mx.template group<1>(&cur.edge, nullptr);
+    const float mu = block_max<BLOCK>(mx.mx, lds);
+    float e[U * V];
+    float part = 0.f;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t k = threadIdx.x + (uint32_t)(u * BLOCK);
+        float f[V];
+        IO::unpack(cur.v[u], f);
+        float t[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i)
+            t[i] = e[u * V + i] = (u < LEAD || k < s.cnt) ? exp_nonpos(f[i] - mu) : 0.f;
+        part += tree_sum<V>(t);
+    }
+    float e_edge = 0.f;
+    if (edge) {
+        e_edge = exp_nonpos(cur.edge - mu);
+        part += e_edge;
+    }
+    const float lambda = 1.0f / block_sum<BLOCK>(part, lds);
+    typename IO::vec *yb = s.yv + s.vb;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t k = threadIdx.x + (uint32_t)(u * BLOCK);
+        if (u < LEAD || k < s.cnt) {
+            float o[V];
+#pragma unroll
+            for (int i = 0; i < V; ++i)
+                o[i] = lambda * e[u * V + i];
+            st<kStoreStream>(yb + k, IO::pack(o));
+        }
+    }
+    if (edge)
+        IO::store1(s.yrow + edge_index(s), lambda * e_edge);
+}
+
+enum { kOnchipTwoPass = 0, kOnchipThreePass = 1 };
+
+template <class IO, int BLOCK, int U, int MODE, int ALGO>
+__device__ __forceinline__ void onchip_row(const Seg<IO> &s, const RowRegs<IO, U> &cur, float *lds)
+{
+    if constexpr (ALGO == kOnchipTwoPass)
+        onchip_row_2p<IO, BLOCK, U, MODE>(s, cur, lds);
+    else
+        onchip_row_3p<IO, BLOCK, U, MODE>(s, cur, lds);
+}
+
 // Marks the point where a row's registers are needed: the compiler places its wait for
 // the loads here.
 template <class IO, int U>
@@ -210,10 +273,9 @@ __device__ __forceinline__ void touch(RowRegs<IO, U> &r)
 // stores: the wait can then leave the stores in flight (as many of them as are issued
 // unconditionally), and they drain while the next row is being computed.  The last row is
 // peeled off so that no load in the loop depends on there being a next row.
-template <class IO, int BLOCK, int U, int MODE>
-__global__ __launch_bounds__(BLOCK) void rows_2p_onchip(const typename IO::elem *x,
-                                                        typename IO::elem *y, int64_t n,
-                                                        int64_t rows)
+template <class IO, int BLOCK, int U, int MODE, int ALGO>
+__global__ __launch_bounds__(BLOCK) void rows_onchip(const typename IO::elem *x,
+                                                     typename IO::elem *y, int64_t n, int64_t rows)
 {
     __shared__ float lds[2 * kMaxWaves];
     int64_t row = blockIdx.x;  // the grid never exceeds the number of rows
@@ -226,12 +288,12 @@ __global__ __launch_bounds__(BLOCK) void rows_2p_onchip(const typename IO::elem 
         RowRegs<IO, U> next;
         load_row<IO, BLOCK, U, MODE>(s_next, next);  // in flight during the current row
         __builtin_amdgcn_sched_barrier(0);           // keep the loads ahead of the arithmetic
-        onchip_row<IO, BLOCK, U, MODE>(s, cur, lds);
+        onchip_row<IO, BLOCK, U, MODE, ALGO>(s, cur, lds);
         touch<IO, U>(next);
         s = s_next;
         cur = next;
     }
-    onchip_row<IO, BLOCK, U, MODE>(s, cur, lds);
+    onchip_row<IO, BLOCK, U, MODE, ALGO>(s, cur, lds);
 }
 
 // ---- chunk path: grid = rows * chunks, rounded up to a multiple of kXcds ---------

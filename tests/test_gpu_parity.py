@@ -228,7 +228,13 @@ def test_nan_poisons_only_its_row(gpu):
 # on-chip variant (row kept in registers between the passes)
 # ---------------------------------------------------------------------------
 
-def test_onchip_f32(gpu, oracle_mod):
+ONCHIP_F32 = [("softmax2p_onchip_f32", TOL_2P), ("softmax3p_onchip_f32", TOL_3P)]
+ONCHIP_BF16 = ["softmax2p_onchip_bf16io", "softmax3p_onchip_bf16io"]
+
+
+@pytest.mark.parametrize("name,tol", ONCHIP_F32)
+def test_onchip_f32(gpu, oracle_mod, name, tol):
+    fn = getattr(gpu, name)
     rng = np.random.default_rng(90)
     cases = [workloads.cfg1(), workloads.cfg1(probes=True), workloads.cfg2(rows=37, n=32768),
              workloads.cfg2(rows=700, n=8192),          # more rows than resident workgroups
@@ -236,42 +242,46 @@ def test_onchip_f32(gpu, oracle_mod):
     for n in EDGE_N + [8191, 8193, 20000, 28001, 32767]:
         cases.append(rng.normal(0, 6, size=(3, n)).astype(np.float32))
     for x in cases:
-        _check(oracle_mod, x, _run(gpu.softmax2p_onchip_f32, x), TOL_2P)
+        _check(oracle_mod, x, _run(fn, x), tol)
     x = workloads.cfg2(rows=9, n=5003)
     for off in (1, 2, 3):                                # rows start anywhere relative to 16 bytes
-        _check(oracle_mod, x, _run(gpu.softmax2p_onchip_f32, x, x_off=off, y_off=off), TOL_2P)
-    _check(oracle_mod, x, _run(gpu.softmax2p_onchip_f32, x, inplace=True), TOL_2P)
-    # same arithmetic as the three-traversal entry point: equal up to summation order
+        _check(oracle_mod, x, _run(fn, x, x_off=off, y_off=off), tol)
+    _check(oracle_mod, x, _run(fn, x, inplace=True), tol)
+    # same arithmetic as the entry point that traverses memory for every pass
     x = workloads.cfg2(rows=40, n=32768)
-    a, b = _run(gpu.softmax2p_onchip_f32, x), _run(gpu.softmax2p_f32, x)
+    a = _run(fn, x)
+    b = _run(gpu.softmax2p_f32 if name.startswith("softmax2p") else gpu.softmax3p_reload_f32, x)
     nz = b > 1e-30
     assert np.max(np.abs(a[nz] - b[nz]) / b[nz]) < 1e-6
 
 
-def test_onchip_bf16(gpu, oracle_mod):
+@pytest.mark.parametrize("name", ONCHIP_BF16)
+def test_onchip_bf16(gpu, oracle_mod, name):
+    fn = getattr(gpu, name)
     rng = np.random.default_rng(91)
     cases = [workloads.cfg5(rows=61, n=21846), workloads.cfg5(rows=1500, n=3000),
              workloads.cfg5(rows=5, n=32768)]
     for n in EDGE_N + [16383, 21841, 32767]:
         cases.append(workloads.f32_to_bf16_bits(rng.normal(0, 6, size=(3, n)).astype(np.float32)).reshape(3, n))
     for x in cases:
-        _check(oracle_mod, x, _run(gpu.softmax2p_onchip_bf16io, x), TOL_BF16, bf16=True)
+        _check(oracle_mod, x, _run(fn, x), TOL_BF16, bf16=True)
     x = workloads.cfg5(rows=7, n=3001)
     for off in (1, 5, 7):
-        _check(oracle_mod, x, _run(gpu.softmax2p_onchip_bf16io, x, x_off=off, y_off=off), TOL_BF16, bf16=True)
-    _check(oracle_mod, x, _run(gpu.softmax2p_onchip_bf16io, x, inplace=True), TOL_BF16, bf16=True)
+        _check(oracle_mod, x, _run(fn, x, x_off=off, y_off=off), TOL_BF16, bf16=True)
+    _check(oracle_mod, x, _run(fn, x, inplace=True), TOL_BF16, bf16=True)
 
 
 def test_onchip_limits(gpu):
     import torch
     t = torch.zeros(40000, dtype=torch.float32, device="cuda")
-    with pytest.raises(gpu.SoftmaxTpError) as e:            # row longer than the register tile
-        gpu.softmax2p_onchip_f32(t, t, 1, 32769)
-    assert e.value.code == gpu.TP_ERR_TOO_LARGE
-    with pytest.raises(gpu.SoftmaxTpError) as e:            # x and y not congruent modulo 16 bytes
-        gpu.softmax2p_onchip_f32(t, t.data_ptr() + 4, 1, 100)
-    assert e.value.code == gpu.TP_ERR_ALIGN
-    gpu.softmax2p_onchip_f32(t, t, 0, 100)
+    for fn in (gpu.softmax2p_onchip_f32, gpu.softmax3p_onchip_f32):
+        with pytest.raises(gpu.SoftmaxTpError) as e:        # row longer than the register tile
+            fn(t, t, 1, 32769)
+        assert e.value.code == gpu.TP_ERR_TOO_LARGE
+        with pytest.raises(gpu.SoftmaxTpError) as e:        # x and y not congruent modulo 16 bytes
+            fn(t, t.data_ptr() + 4, 1, 100)
+        assert e.value.code == gpu.TP_ERR_ALIGN
+        fn(t, t, 0, 100)
     torch.cuda.synchronize()
     assert float(t.abs().sum()) == 0.0
 
