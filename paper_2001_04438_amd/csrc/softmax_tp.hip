@@ -44,8 +44,17 @@ static bool valid_unroll(int64_t u, int elem_bytes)
 
 // Rows path: the largest tile (block * unroll vectors per round) that wastes at
 // most 15 % of its last round on the row.
+constexpr int64_t kWaveRowMaxVecs = 256;  // rows up to this many vectors get a wave each
+
 static void rows_shape(int64_t nvec, int elem_bytes, softmax_tp_shape_t *s)
 {
+    s->chunk_vecs = 0;
+    s->chunks = 1;
+    if (nvec <= kWaveRowMaxVecs && !g_tune.block_rows && !g_tune.unroll_rows) {
+        s->block = kWave;  // one wave per row, kWavesPerGroup rows per workgroup
+        s->unroll = nvec <= 2 * kWave ? 2 : 4;
+        return;
+    }
     static const int cand_f32[][2] = {{1024, 8}, {1024, 4}, {512, 4}, {512, 2}, {256, 2}};
     static const int cand_bf16[][2] = {{1024, 4}, {1024, 2}, {512, 2}, {256, 2}, {256, 2}};
     const int(*cand)[2] = elem_bytes == 4 ? cand_f32 : cand_bf16;
@@ -62,8 +71,6 @@ static void rows_shape(int64_t nvec, int elem_bytes, softmax_tp_shape_t *s)
     }
     if (g_tune.block_rows) s->block = (int32_t)g_tune.block_rows;
     if (g_tune.unroll_rows) s->unroll = (int32_t)g_tune.unroll_rows;
-    s->chunk_vecs = 0;
-    s->chunks = 1;
 }
 
 static int chunk_shape(int64_t rows, int64_t nvec, int block, int unroll, int64_t chunk_vecs,
@@ -116,7 +123,8 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
         p->path = 1;
         rows_shape(nvec, elem_bytes, &p->rows);
         p->launches = 1;
-        return valid_block(p->rows.block) && valid_unroll(p->rows.unroll, elem_bytes)
+        return (p->rows.block == kWave || valid_block(p->rows.block)) &&
+                       valid_unroll(p->rows.unroll, elem_bytes)
                    ? TP_OK : TP_ERR_TUNING;
     }
 
@@ -261,6 +269,27 @@ template <class IO>
 static int run_rows(Algo algo, const softmax_tp_plan_t &plan, const typename IO::elem *x,
                     typename IO::elem *y, int64_t rows, int64_t n, hipStream_t st)
 {
+    if (plan.rows.block == kWave) {  // short rows: a wave per row
+        const dim3 wgrid((uint32_t)((rows + kWavesPerGroup - 1) / kWavesPerGroup));
+        const dim3 wblock(kWave * kWavesPerGroup);
+#define TP_WAVES(UU)                                                                          \
+    do {                                                                                      \
+        if (algo == kTwoPass)                                                                 \
+            hipLaunchKernelGGL((waves_2p<IO, UU>), wgrid, wblock, 0, st, x, y, n, rows);      \
+        else if (algo == kRecompute)                                                          \
+            hipLaunchKernelGGL((waves_3p_recompute<IO, UU>), wgrid, wblock, 0, st, x, y, n,   \
+                               rows);                                                         \
+        else                                                                                  \
+            hipLaunchKernelGGL((waves_3p_reload<IO, UU>), wgrid, wblock, 0, st, x, y, n,      \
+                               rows);                                                         \
+    } while (0)
+        if (plan.rows.unroll == 2)
+            TP_WAVES(2);
+        else
+            TP_WAVES(4);
+#undef TP_WAVES
+        return launch_status();
+    }
     const dim3 grid((uint32_t)rows);
     return with_shape<IO>(plan.rows, [&](auto B, auto U) {
         if (algo == kTwoPass)
@@ -442,29 +471,32 @@ struct OnchipShape {
 };
 
 // A row must fit block * unroll vectors.  lo / hi bound the number of whole vectors a row
-// can have (it depends on where the row starts relative to a 16-byte boundary).  Preferred:
-// a tile the rows fill exactly, then tiles whose first unroll - 1 slots every row fills
-// (least padding first), then the catch-all with 1024 threads.
+// can have (it depends on where the row starts relative to a 16-byte boundary).  Candidates
+// are tiles the rows fill exactly (kTileFull) and tiles whose first unroll - 1 slots every
+// row fills (kTileMostly); the one with the least padding wins, then the unroll closest to
+// 4, then the smaller block.  If neither kind exists: the catch-all with 1024 threads.
 static bool onchip_shape(int64_t lo, int64_t hi, bool exact, int unroll_max, OnchipShape *out)
 {
-    static const int blocks[] = {1024, 512, 256};
+    static const int blocks[] = {256, 512, 1024};
     bool found = false;
-    int64_t best_pad = 0;
+    int64_t best_key = 0;
     for (int b : blocks) {
         const int64_t u = hi <= b ? 1 : (hi + b - 1) / b;
         if (u > unroll_max)
             continue;
-        if (exact && hi == b * u && (u == 1 || u == 2 || u == 4 || u == 8)) {
-            *out = OnchipShape{b, (int)u, kTileFull};
-            return true;
-        }
-        if ((u - 1) * b > lo)
+        int mode;
+        if (exact && hi == b * u && (u == 1 || u == 2 || u == 4 || u == 8))
+            mode = kTileFull;
+        else if ((u - 1) * b <= lo)
+            mode = kTileMostly;
+        else
             continue;
         const int64_t pad = b * u - hi;
-        if (!found || pad < best_pad) {
+        const int64_t key = (pad << 8) + ((u > 4 ? u - 4 : 4 - u) << 2) + (mode == kTileFull ? 0 : 1);
+        if (!found || key < best_key) {
             found = true;
-            best_pad = pad;
-            *out = OnchipShape{b, (int)u, kTileMostly};
+            best_key = key;
+            *out = OnchipShape{b, (int)u, mode};
         }
     }
     if (found)

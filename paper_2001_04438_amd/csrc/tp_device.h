@@ -359,8 +359,10 @@ __device__ __forceinline__ void st(VEC *p, VEC v)
 // which consumes G elements (and, if kWrite, produces G outputs).  Full rounds
 // hand over G = U*V elements at once; the last, partly filled round hands over
 // the vectors that exist one at a time.
+// `tid` is the thread's index among the BLOCK threads that share the segment (the
+// workgroup by default; a single wave when one wave owns a row).
 template <class IO, int BLOCK, int U, bool NT_LOAD, bool NT_STORE, class P>
-__device__ __forceinline__ void stream(const Seg<IO> &s, P &p)
+__device__ __forceinline__ void stream(const Seg<IO> &s, P &p, uint32_t tid = threadIdx.x)
 {
     using vec = typename IO::vec;
     constexpr int V = IO::V;
@@ -368,7 +370,7 @@ __device__ __forceinline__ void stream(const Seg<IO> &s, P &p)
     const vec *xb = s.xv + s.vb;
     vec *yb = s.yv + s.vb;
     const uint32_t cnt = s.cnt;
-    uint32_t k = threadIdx.x;
+    uint32_t k = tid;
 
     for (; k + (uint32_t)((U - 1) * BLOCK) < cnt; k += (uint32_t)(U * BLOCK)) {
         vec v[U];
@@ -408,9 +410,8 @@ __device__ __forceinline__ void stream(const Seg<IO> &s, P &p)
     if (s.edges) {
         const int64_t ntail = s.n - s.tail0;
         const int64_t nedge = s.head + ntail;
-        if ((int64_t)threadIdx.x < nedge) {
-            const int64_t i = (int)threadIdx.x < s.head ? (int64_t)threadIdx.x
-                                                        : s.tail0 + ((int64_t)threadIdx.x - s.head);
+        if ((int64_t)tid < nedge) {
+            const int64_t i = (int)tid < s.head ? (int64_t)tid : s.tail0 + ((int64_t)tid - s.head);
             float f = IO::load1(s.xrow + i), o;
             p.template group<1>(&f, &o);
             if constexpr (P::kWrite)

@@ -68,6 +68,62 @@ __global__ __launch_bounds__(BLOCK) void rows_3p_reload(const typename IO::elem 
     stream<IO, BLOCK, U, kLoadStream, kStoreStream>(sy, sc);
 }
 
+// ---- short rows: one wave per row, several rows per workgroup --------------------------
+//
+// Rows of at most a few hundred vectors cannot keep a whole workgroup busy.  Here every
+// wave owns a row of its own: no LDS, no barrier, the wave reduction is the row reduction.
+
+constexpr int kWavesPerGroup = 4;
+
+#define TP_WAVE_ROW_PROLOGUE                                                                 \
+    const int64_t row = (int64_t)blockIdx.x * kWavesPerGroup + threadIdx.x / kWave;          \
+    if (row >= rows)                                                                         \
+        return;                                                                              \
+    const uint32_t lane = threadIdx.x & (kWave - 1);                                         \
+    const Seg<IO> s = make_seg<IO>(x, y, n, row, 0, INT64_MAX / 2);
+
+template <class IO, int U>
+__global__ __launch_bounds__(kWave *kWavesPerGroup) void waves_2p(const typename IO::elem *x,
+                                                                   typename IO::elem *y,
+                                                                   int64_t n, int64_t rows)
+{
+    TP_WAVE_ROW_PROLOGUE
+    PairSum acc;
+    stream<IO, kWave, U, kLoadKeep, kStoreStream>(s, acc, lane);
+    wave_pair(acc.m, acc.n);
+    PairOut out(1.0f / acc.m, acc.n);
+    stream<IO, kWave, U, kLoadStream, kStoreStream>(s, out, lane);
+}
+
+template <class IO, int U>
+__global__ __launch_bounds__(kWave *kWavesPerGroup) void waves_3p_recompute(
+    const typename IO::elem *x, typename IO::elem *y, int64_t n, int64_t rows)
+{
+    TP_WAVE_ROW_PROLOGUE
+    MaxOf mx;
+    stream<IO, kWave, U, kLoadKeep, kStoreStream>(s, mx, lane);
+    const float mu = wave_max(mx.mx);
+    SumExp se{mu};
+    stream<IO, kWave, U, kLoadKeep, kStoreStream>(s, se, lane);
+    ExpScale es(mu, 1.0f / wave_sum(se.s));
+    stream<IO, kWave, U, kLoadStream, kStoreStream>(s, es, lane);
+}
+
+template <class IO, int U>
+__global__ __launch_bounds__(kWave *kWavesPerGroup) void waves_3p_reload(
+    const typename IO::elem *x, typename IO::elem *y, int64_t n, int64_t rows)
+{
+    TP_WAVE_ROW_PROLOGUE
+    MaxOf mx;
+    stream<IO, kWave, U, kLoadKeep, kStoreStream>(s, mx, lane);
+    const float mu = wave_max(mx.mx);
+    ExpStoreSum ess{mu};
+    stream<IO, kWave, U, kLoadStream, kStoreKeep>(s, ess, lane);
+    const Seg<IO> sy = make_seg<IO>(y, y, n, row, 0, INT64_MAX / 2);
+    Scale sc{1.0f / wave_sum(ess.s)};
+    stream<IO, kWave, U, kLoadStream, kStoreStream>(sy, sc, lane);
+}
+
 // ---- on-chip rows: the row stays in registers between the passes -------------------
 //
 // For rows of at most BLOCK * U vectors.  A workgroup walks rows blockIdx.x,

@@ -169,6 +169,30 @@ def test_edge_lengths_bf16(gpu, oracle_mod):
 
 
 @pytest.mark.parametrize("name,tol", ALGOS_F32)
+def test_short_rows_one_wave_each(gpu, oracle_mod, name, tol):
+    rng = np.random.default_rng(83)
+    for rows, n in ((1001, 100), (4097, 256), (6, 1024), (513, 1021), (3000, 33), (50, 1)):
+        assert gpu.softmax_tp_plan(rows, n).rows.block == 64
+        x = rng.normal(0, 5, size=(rows, n)).astype(np.float32)
+        _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
+    x = rng.normal(0, 5, size=(333, 255)).astype(np.float32)
+    _check(oracle_mod, x, _run(getattr(gpu, name), x, x_off=1, y_off=1), tol)
+    _check(oracle_mod, x, _run(getattr(gpu, name), x, x_off=1, y_off=2), tol)   # element-wise format
+    _check(oracle_mod, x, _run(getattr(gpu, name), x, inplace=True), tol)
+
+
+def test_short_rows_one_wave_each_bf16(gpu, oracle_mod):
+    rng = np.random.default_rng(84)
+    for name in ("softmax2p_bf16io", "softmax3p_recompute_bf16io", "softmax3p_reload_bf16io"):
+        for rows, n in ((1001, 100), (4097, 512), (7, 2048), (513, 2041)):
+            assert gpu.softmax_tp_plan(rows, n, 2).rows.block == 64
+            x = workloads.f32_to_bf16_bits(rng.normal(0, 5, size=(rows, n)).astype(np.float32)).reshape(rows, n)
+            _check(oracle_mod, x, _run(getattr(gpu, name), x), TOL_BF16, bf16=True)
+        x = workloads.cfg5(rows=77, n=1003)
+        _check(oracle_mod, x, _run(getattr(gpu, name), x, x_off=3, y_off=3), TOL_BF16, bf16=True)
+
+
+@pytest.mark.parametrize("name,tol", ALGOS_F32)
 def test_unaligned_and_incongruent_pointers_f32(gpu, oracle_mod, name, tol):
     rng = np.random.default_rng(79)
     x = rng.normal(0, 5, size=(4, 1001)).astype(np.float32)

@@ -101,7 +101,8 @@ def test_planner_covers_odd_shapes(B):
             V = (16 // s) if congruent else 1
             assert p.vector_elems == V
             if p.path == 1:
-                assert n * s <= 256 * 1024 and p.rows.block in (256, 512, 1024)
+                assert n * s <= 256 * 1024 and p.rows.block in (64, 256, 512, 1024)
+                assert (p.rows.block == 64) == (-(-n // V) <= 256)   # short rows: a wave each
             else:
                 nvec = -(-n // V)
                 for shape in (p.reduce, p.map, p.mapsum):
