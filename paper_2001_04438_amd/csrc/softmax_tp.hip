@@ -30,7 +30,7 @@ static Tuning g_tune;
 
 constexpr int64_t kRowsPathMaxBytes = 256 * 1024;  // longest row one workgroup takes
 constexpr int64_t kRowsPathMinRows = 32;           // fewer rows than this cannot fill the chip
-constexpr int64_t kSmallRowBytes = 32 * 1024;      // ... unless the rows are this short
+constexpr int64_t kSmallRowBytes = 128 * 1024;     // ... unless the rows are this short (one launch wins)
 constexpr int64_t kTargetReduce = 1024;            // workgroups of a read-only pass (4 per CU)
 constexpr int64_t kNtFirstBytes = (int64_t)512 << 20;  // inputs beyond this outlive every cache
 constexpr int64_t kGridMax = 0x7FFFFFF0;           // grids are rounded up to a multiple of kXcds
