@@ -116,9 +116,16 @@ def run_workload(torch, B, W, name, steps, warmup, full):
     for vname, fn in variants:
         call = lambda i, fn=fn: fn(xs[i], ys[i], rows, n)
         wall_ms, ev_ms = time_calls(torch, call, steps, warmup, sets)
+        # the protocol of Section 6.2 reports a median over repetitions: per-call event times,
+        # cold (rotating buffer sets) and warm (the same buffers every call)
+        _, med_ms, min_ms = per_launch_ms(torch, call, max(steps, 25), sets)
+        _, warm_med_ms, _ = per_launch_ms(torch, lambda i, fn=fn: fn(xs[0], ys[0], rows, n),
+                                          max(steps, 25), 1)
         alg_bytes = BYTES_PER_ELEM[vname] * elems * s
         out["variants"][vname] = {
             "ms_per_step": wall_ms, "ms_per_step_events": ev_ms,
+            "ms_per_call_median": med_ms, "ms_per_call_min": min_ms,
+            "ms_per_call_median_warm": warm_med_ms,
             "algorithmic_bytes": alg_bytes, "GBps": alg_bytes / wall_ms / 1e6,
             "elements_per_s": elems / wall_ms * 1e3,
             "frac_of_hbm_peak": alg_bytes / wall_ms / 1e6 / HBM_PEAK_GBS,
@@ -175,6 +182,17 @@ def calibration(torch, B, steps, warmup):
     return res
 
 
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(x_host, y_host, bf16, tol):
     """Times the oracle as it stands on the host cores and checks the GPU output with it."""
     import oracle
@@ -186,8 +204,15 @@ def cpu_baseline(x_host, y_host, bf16, tol):
     cmp_ = oracle.compare(x_host, y_host, tol, bf16=bf16)  # recomputes mu, S, then every p_i
     t_cmp = time.perf_counter() - t0
     # softmax = statistics pass + one exp and one division per element: the comparator does
-    # exactly that work (plus the comparison), so its time stands for a full oracle softmax
-    return cores, t_stats, t_cmp, cmp_
+    # exactly that work (plus the comparison), so its time stands for a full oracle softmax.
+    # Single-thread figure on a prefix of the same data (2^22 elements of the first row).
+    rows, n = x_host.shape
+    m1 = min(n, 1 << 22)
+    xs, ys = x_host[:1, :m1], y_host[:1, :m1]
+    t0 = time.perf_counter()
+    oracle.compare(xs, ys, 1.0, bf16=bf16, threads=1)
+    t_one = time.perf_counter() - t0
+    return cores, t_stats, t_cmp, cmp_, m1 / t_one
 
 
 def main():
@@ -215,7 +240,7 @@ def main():
     head, x_host, y_host = run_workload(torch, B, W, args.workload, args.steps, args.warmup, True)
     bf16 = head["dtype"] == "bf16"
     tol = 1e-2 if bf16 else 4e-6
-    cores, t_stats, t_cmp, cmp_ = cpu_baseline(x_host, y_host, bf16, tol)
+    cores, t_stats, t_cmp, cmp_, one_thread_eps = cpu_baseline(x_host, y_host, bf16, tol)
     log(f"[bench] oracle on {cores} threads: stats {t_stats:.2f}s, softmax+compare {t_cmp:.2f}s; "
         f"GPU max_rel_err={cmp_.max_rel_err:.3e} ok={cmp_.ok()}")
     del x_host, y_host
@@ -252,12 +277,15 @@ def main():
         "cpu_baseline": {
             "value": 3 * elems * s / t_cmp / 1e9, "unit": "GB/s (same 3*N*s byte count)",
             "elements_per_s": elems / t_cmp, "seconds": t_cmp, "cores": cores, "kind": "oracle",
+            "cpu": cpu_model(), "single_thread_elements_per_s": one_thread_eps,
             "sample": f"the whole {args.workload} input, one oracle softmax fused with the comparison "
                       f"of the GPU output (statistics pass alone: {t_stats:.2f}s)",
         },
         "parity": {"max_rel_err": cmp_.max_rel_err, "tolerance": tol, "ok": bool(cmp_.ok()),
                    "max_row_sum_dev": cmp_.max_row_sum_dev},
-        "variants": {k: {kk: v[kk] for kk in ("ms_per_step", "GBps", "elements_per_s", "frac_of_hbm_peak")}
+        "variants": {k: {kk: v[kk] for kk in ("ms_per_step", "ms_per_call_median", "ms_per_call_min",
+                                              "ms_per_call_median_warm", "GBps", "elements_per_s",
+                                              "frac_of_hbm_peak")}
                      for k, v in head["variants"].items()},
         "passes": {k: head[k] for k in ("pass1_ms", "pass2_ms", "kernel_ms") if k in head},
     }
@@ -275,7 +303,9 @@ def main():
             others[name] = {
                 "shape": f"{o['rows']} x {o['n']} {o['dtype']}", "path": o["plan"]["path"],
                 "buffer_sets": o["buffer_sets"],
-                "variants": {k: {kk: v[kk] for kk in ("ms_per_step", "GBps", "frac_of_hbm_peak")}
+                "variants": {k: {kk: v[kk] for kk in ("ms_per_step", "ms_per_call_median",
+                                                      "ms_per_call_median_warm", "GBps",
+                                                      "frac_of_hbm_peak")}
                              for k, v in o["variants"].items()},
                 "dominant": o["dominant"]}
         result["other_workloads"] = others

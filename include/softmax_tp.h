@@ -196,6 +196,12 @@ TP_API int softmax_tp_plan(int64_t rows, int64_t n, int32_t elem_bytes, int32_t 
  */
 TP_API int softmax_tp_tune(const char *key, int64_t value);
 
+/*
+ * Allocates (or grows) the workspace a later softmax call with this shape on this stream
+ * would need, so that the call itself does not allocate.  Shapes on the rows path need none.
+ */
+TP_API int softmax_tp_reserve(int64_t rows, int64_t n, int32_t elem_bytes, void *stream);
+
 /* Frees every workspace the library holds (synchronises the device). */
 TP_API int softmax_tp_release(void);
 

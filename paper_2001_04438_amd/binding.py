@@ -37,6 +37,7 @@ ENTRY_POINTS = {
     "softmax_tp_stream_scale_f32": [_vp, _vp, ctypes.c_float, _i64, _vp],
     "softmax_tp_plan": [_i64, _i64, ctypes.c_int32, ctypes.c_int32, _vp],
     "softmax_tp_tune": [ctypes.c_char_p, _i64],
+    "softmax_tp_reserve": [_i64, _i64, ctypes.c_int32, _vp],
     "softmax_tp_release": [],
     "softmax_tp_strerror": [ctypes.c_int],
 }
@@ -229,6 +230,10 @@ def softmax_tp_tune_reset():
     """Restores every planner parameter to its default."""
     for key in TUNE_KEYS:
         softmax_tp_tune(key, 0)
+
+
+def softmax_tp_reserve(rows, n, elem_bytes=4, stream=None):
+    _check("softmax_tp_reserve", lib().softmax_tp_reserve(rows, n, elem_bytes, _stream(stream)))
 
 
 def softmax_tp_release():

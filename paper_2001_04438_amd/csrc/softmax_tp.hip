@@ -863,6 +863,16 @@ int softmax_tp_tune(const char *key, int64_t value)
     return TP_ERR_TUNING;
 }
 
+int softmax_tp_reserve(int64_t rows, int64_t n, int32_t elem_bytes, void *stream)
+{
+    softmax_tp_plan_t plan;
+    int rc = make_plan(rows, n, elem_bytes, true, 0, &plan);
+    if (rc != TP_OK || plan.workspace_bytes == 0)
+        return rc;
+    float *ws = nullptr;
+    return workspace((hipStream_t)stream, (size_t)plan.workspace_bytes, &ws);
+}
+
 int softmax_tp_release(void)
 {
     std::lock_guard<std::mutex> lock(g_ws_mutex);

@@ -446,6 +446,18 @@ def test_bitwise_reproducible(gpu):
         assert np.array_equal(a, b)
 
 
+def test_reserve_and_release(gpu, oracle_mod):
+    gpu.softmax_tp_release()
+    gpu.softmax_tp_reserve(3, 500_000)            # chunk path: workspace allocated up front
+    gpu.softmax_tp_reserve(100, 1000)             # rows path: nothing to allocate
+    x = workloads.cfg3(rows=3, n=500_000)
+    _check(oracle_mod, x, _run(gpu.softmax2p_f32, x), TOL_2P)
+    gpu.softmax_tp_release()
+    _check(oracle_mod, x, _run(gpu.softmax3p_reload_f32, x), TOL_3P)   # allocates again on demand
+    with pytest.raises(gpu.SoftmaxTpError):
+        gpu.softmax_tp_reserve(-1, 5)
+
+
 def test_calibration_streams(gpu):
     import torch
     n = (1 << 22) + 5

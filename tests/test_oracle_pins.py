@@ -363,3 +363,47 @@ def test_comparator_bf16(oracle_mod):
     c8 = oracle_mod.compare(x[:1], y[:1], 1e-2, bf16=True, threads=8)
     assert c1.max_rel_err == c8.max_rel_err and c1.n_total == c8.n_total == 1001
     assert abs(c1.max_row_sum_dev - c8.max_row_sum_dev) < 1e-15
+
+
+# --------------------------------------------------------------------------
+# the oracle's C code under the address and undefined-behaviour sanitizers
+# --------------------------------------------------------------------------
+
+def test_oracle_under_sanitizers(tmp_path):
+    import subprocess
+    import sys
+    here = os.path.dirname(os.path.abspath(__file__))
+    root = os.path.dirname(here)
+    lib = tmp_path / "liboracle_san.so"
+    srcs = [os.path.join(root, "oracle", f) for f in ("softmax_oracle.c", "twopass_model.c")]
+    subprocess.run(["gcc", "-std=c11", "-O1", "-g", "-fPIC", "-shared", "-fno-fast-math",
+                    "-ffp-contract=off", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                    "-o", str(lib), *srcs, "-lm", "-lpthread"], check=True)
+    script = f"""
+import ctypes, numpy as np
+L = ctypes.CDLL({str(lib)!r})
+vp, i64 = ctypes.c_void_p, ctypes.c_int64
+rng = np.random.default_rng(0)
+for rows, n, threads in ((1, 1, 1), (3, 17, 2), (2, 4099, 8), (1, 100003, 5), (7, 33, 16)):
+    x = rng.normal(0, 30, size=(rows, n)).astype(np.float32)
+    p = np.zeros((rows, n), dtype=np.longdouble)
+    L.oracle_softmax_f32(x.ctypes.data_as(vp), i64(rows), i64(n), p.ctypes.data_as(vp), threads)
+    assert abs(float(p.sum()) - rows) < 1e-9
+    y = p.astype(np.float32)
+    buf = (ctypes.c_char * 256)()
+    L.oracle_compare_f32(x.ctypes.data_as(vp), y.ctypes.data_as(vp), i64(rows), i64(n),
+                         ctypes.c_double(4e-6), buf, threads)
+    h = (x.view(np.uint32) >> 16).astype(np.uint16)
+    L.oracle_softmax_bf16(h.ctypes.data_as(vp), i64(rows), i64(n), p.ctypes.data_as(vp), threads)
+    assert abs(float(p.sum()) - rows) < 1e-9
+d = np.linspace(-50, 50, 1001)
+yd = np.zeros_like(d)
+L.model_twopass(d.ctypes.data_as(vp), yd.ctypes.data_as(vp), i64(d.size))
+assert abs(yd.sum() - 1) < 1e-12
+print("sanitized run ok")
+"""
+    asan = subprocess.run(["gcc", "-print-file-name=libasan.so"], capture_output=True, text=True).stdout.strip()
+    preload = asan + (":" + os.environ["LD_PRELOAD"] if os.environ.get("LD_PRELOAD") else "")
+    env = dict(os.environ, LD_PRELOAD=preload, ASAN_OPTIONS="detect_leaks=0:verify_asan_link_order=0")
+    res = subprocess.run([sys.executable, "-c", script], env=env, capture_output=True, text=True)
+    assert res.returncode == 0 and "sanitized run ok" in res.stdout, res.stderr[-2000:]
