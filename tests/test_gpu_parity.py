@@ -446,6 +446,39 @@ def test_bitwise_reproducible(gpu):
         assert np.array_equal(a, b)
 
 
+def test_random_shapes_all_entry_points(gpu, oracle_mod):
+    """Seeded random (rows, n, pointer offset) across every path boundary."""
+    rng = np.random.default_rng(20010443)
+    f32 = [("softmax2p_f32", TOL_2P), ("softmax3p_recompute_f32", TOL_3P), ("softmax3p_reload_f32", TOL_3P),
+           ("softmax2p_onchip_f32", TOL_2P), ("softmax3p_onchip_f32", TOL_3P)]
+    bf16 = ["softmax2p_bf16io", "softmax3p_recompute_bf16io", "softmax3p_reload_bf16io",
+            "softmax2p_onchip_bf16io", "softmax3p_onchip_bf16io"]
+    for trial in range(40):
+        kind = trial % 4
+        if kind == 0:      # short rows, many of them
+            rows, n = int(rng.integers(1, 3000)), int(rng.integers(1, 1100))
+        elif kind == 1:    # rows-path sizes
+            rows, n = int(rng.integers(1, 200)), int(rng.integers(1000, 66000))
+        elif kind == 2:    # chunk path, few long rows
+            rows, n = int(rng.integers(1, 6)), int(rng.integers(70_000, 900_000))
+        else:              # around the register-tile limits of the on-chip kernels
+            rows, n = int(rng.integers(1, 600)), int(rng.choice([4095, 4096, 4097, 8191, 8192, 12289,
+                                                                 16384, 20481, 24577, 32767, 32768]))
+        off = int(rng.integers(0, 4))
+        scale = float(rng.choice([0.5, 4.0, 30.0]))
+        x = (rng.standard_normal((rows, n)) * scale + rng.uniform(-50, 50, size=(rows, 1))).astype(np.float32)
+        xb = workloads.f32_to_bf16_bits(x).reshape(rows, n)
+        print(f"trial {trial}: rows={rows} n={n} off={off} scale={scale}", flush=True)
+        for name, tol in f32:
+            if "onchip" in name and n > 32768:
+                continue
+            _check(oracle_mod, x, _run(getattr(gpu, name), x, x_off=off, y_off=off), tol)
+        for name in bf16:
+            if "onchip" in name and n > 32768:
+                continue
+            _check(oracle_mod, xb, _run(getattr(gpu, name), xb, x_off=2 * off, y_off=2 * off), TOL_BF16, bf16=True)
+
+
 def test_reserve_and_release(gpu, oracle_mod):
     gpu.softmax_tp_release()
     gpu.softmax_tp_reserve(3, 500_000)            # chunk path: workspace allocated up front
