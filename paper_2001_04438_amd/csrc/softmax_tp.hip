@@ -33,7 +33,10 @@ constexpr int64_t kRowsPathMinRows = 32;           // fewer rows than this canno
 constexpr int64_t kSmallRowBytes = 128 * 1024;     // ... unless the rows are this short (one launch wins)
 constexpr int64_t kTargetReduce = 1024;            // workgroups of a read-only pass (4 per CU)
 constexpr int64_t kNtFirstBytes = (int64_t)512 << 20;  // inputs beyond this outlive every cache
-constexpr int64_t kGridMax = 0x7FFFFFF0;           // grids are rounded up to a multiple of kXcds
+// A launch may hold at most 2^32 - 1 threads in all (and 2^31 - 1 workgroups); grids are
+// rounded up to a multiple of kXcds, hence the margin.
+constexpr int64_t kThreadsMax = 0xFFFFFFFFll - 16 * 1024;
+constexpr int64_t kGridMax = 0x7FFFFFF0;
 constexpr int64_t kChunkVecsMax = (int64_t)1 << 26;  // a chunk is indexed with 32-bit offsets
 
 static bool valid_block(int64_t b) { return b == 256 || b == 512 || b == 1024; }
@@ -77,13 +80,21 @@ static int chunk_shape(int64_t rows, int64_t nvec, int block, int unroll, int64_
                        softmax_tp_shape_t *s)
 {
     const int64_t tile = (int64_t)block * unroll;
+    // the launch limits bound the number of chunks per row; longer chunks make up for it
+    int64_t chunks_max = kThreadsMax / block / rows;
+    if (chunks_max > kGridMax / rows) chunks_max = kGridMax / rows;
+    if (chunks_max < 1)
+        return TP_ERR_TOO_LARGE;
+    const int64_t cv_min = (nvec + chunks_max - 1) / chunks_max;
+    const int64_t cv_max = kChunkVecsMax / tile * tile;
+    if (chunk_vecs < cv_min) chunk_vecs = cv_min;
     int64_t cv = (chunk_vecs + tile - 1) / tile * tile;
     if (cv < tile) cv = tile;
-    if (cv > kChunkVecsMax) cv = kChunkVecsMax / tile * tile;
+    if (cv > cv_max) cv = cv_max;
+    if (cv < cv_min)
+        return TP_ERR_TOO_LARGE;
     int64_t chunks = (nvec + cv - 1) / cv;
     if (chunks < 1) chunks = 1;
-    if (chunks > kGridMax / rows)
-        return TP_ERR_TOO_LARGE;
     s->block = block;
     s->unroll = unroll;
     s->chunk_vecs = cv;
@@ -122,6 +133,10 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
             return TP_ERR_TOO_LARGE;
         p->path = 1;
         rows_shape(nvec, elem_bytes, &p->rows);
+        // one workgroup per row (a wave-per-row launch has a quarter of the workgroups)
+        const int64_t threads = p->rows.block == kWave ? kWave : p->rows.block;
+        if (rows > kThreadsMax / threads)
+            return TP_ERR_TOO_LARGE;
         p->launches = 1;
         return (p->rows.block == kWave || valid_block(p->rows.block)) &&
                        valid_unroll(p->rows.unroll, elem_bytes)

@@ -94,7 +94,7 @@ __device__ __forceinline__ float wave_sum(float v)
 }
 
 // 64 pairs -> one: wave maximum of the exponents, each lane rescales its mantissa
-// to it, wave sum of the mantissas.  Same result as 63 pairwise additions.
+// to it, wave sum of the mantissas: 63 pair additions of Algorithm 3 done as a tree.
 __device__ __forceinline__ void wave_pair(float &m, float &n)
 {
     float nw = wave_max(n);

@@ -110,6 +110,13 @@ def test_planner_covers_odd_shapes(B):
     assert B.softmax_tp_plan(0, 5).path == 0 and B.softmax_tp_plan(5, 0).path == 0
     big = B.softmax_tp_plan(1, 1 << 40)
     assert big.path == 2 and big.map.chunks * big.map.chunk_vecs >= (1 << 38)
+    # a launch holds fewer than 2^32 threads: shapes beyond that are refused, not truncated
+    assert big.map.chunks * big.map.block < 2 ** 32 and big.map.chunk_vecs > 2048
+    for rows, n in ((1 << 23, 8192), (1, 1 << 60), (1 << 27, 64)):
+        with pytest.raises(B.SoftmaxTpError) as e:
+            B.softmax_tp_plan(rows, n)
+        assert e.value.code == B.TP_ERR_TOO_LARGE
+    assert B.softmax_tp_plan(1 << 21, 8192).path == 1
 
 
 def test_tuning_keys(B):
