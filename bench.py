@@ -86,33 +86,36 @@ def load_traffic(workload, kernel):
 def run_workload(torch, B, W, name, steps, warmup, full):
     import numpy as np
 
-    rows, n = W.SHAPES[name]
-    bf16 = W.DTYPES[name] == "bf16"
-    s = 2 if bf16 else 4
+    # "<cfg>_f16": the same values stored as IEEE binary16 instead of the workload's own format
+    base, f16 = (name[:-4], True) if name.endswith("_f16") else (name, False)
+    rows, n = W.SHAPES[base]
+    bf16 = W.DTYPES[base] == "bf16" and not f16
+    fmt = "f16" if f16 else "bf16" if bf16 else "f32"
+    s = 4 if fmt == "f32" else 2
     t0 = time.perf_counter()
-    x_host = W.make(name)
-    log(f"[bench] {name}: generated {rows}x{n} {W.DTYPES[name]} in {time.perf_counter() - t0:.1f}s")
+    x_host = W.make(base)
+    if f16:
+        vals = W.bf16_bits_to_f32(x_host) if W.DTYPES[base] == "bf16" else x_host
+        x_host = W.f32_to_f16_bits(vals).reshape(rows, n)
+    log(f"[bench] {name}: generated {rows}x{n} {fmt} in {time.perf_counter() - t0:.1f}s")
     flat = x_host.reshape(-1)
-    host_t = torch.from_numpy(flat.view(np.int16) if bf16 else flat)
+    host_t = torch.from_numpy(flat.view(np.int16) if s == 2 else flat)
     footprint = 2 * flat.size * s
     sets = 1 if footprint >= (1 << 30) else int(min(8, -(-(1 << 30) // footprint)))
     xs = [host_t.cuda() for _ in range(sets)]
     ys = [torch.empty_like(xs[0]) for _ in range(sets)]
     elems = rows * n
     plan = B.softmax_tp_plan(rows, n, s, True)
-    out = {"rows": rows, "n": n, "dtype": "bf16" if bf16 else "f32", "buffer_sets": sets,
+    out = {"rows": rows, "n": n, "dtype": fmt, "buffer_sets": sets,
            "plan": plan.as_dict(), "variants": {}}
 
-    variants = [("softmax2p", B.softmax2p_bf16io if bf16 else B.softmax2p_f32)]
-    if bf16:
-        variants += [("softmax3p_recompute", B.softmax3p_recompute_bf16io),
-                     ("softmax3p_reload", B.softmax3p_reload_bf16io)]
-    else:
-        variants += [("softmax3p_recompute", B.softmax3p_recompute_f32),
-                     ("softmax3p_reload", B.softmax3p_reload_f32)]
+    suffix = {"f32": "_f32", "bf16": "_bf16io", "f16": "_f16io"}[fmt]
+    variants = [("softmax2p", getattr(B, "softmax2p" + suffix)),
+                ("softmax3p_recompute", getattr(B, "softmax3p_recompute" + suffix)),
+                ("softmax3p_reload", getattr(B, "softmax3p_reload" + suffix))]
     if n <= 32768:  # short rows: also the variant that keeps the row in registers
-        variants += [("softmax2p_onchip", B.softmax2p_onchip_bf16io if bf16 else B.softmax2p_onchip_f32),
-                     ("softmax3p_onchip", B.softmax3p_onchip_bf16io if bf16 else B.softmax3p_onchip_f32)]
+        variants += [("softmax2p_onchip", getattr(B, "softmax2p_onchip" + suffix)),
+                     ("softmax3p_onchip", getattr(B, "softmax3p_onchip" + suffix))]
     for vname, fn in variants:
         call = lambda i, fn=fn: fn(xs[i], ys[i], rows, n)
         wall_ms, ev_ms = time_calls(torch, call, steps, warmup, sets)
@@ -133,7 +136,7 @@ def run_workload(torch, B, W, name, steps, warmup, full):
         log(f"[bench] {name} {vname}: {wall_ms:.4f} ms/step, {alg_bytes / wall_ms / 1e6:.0f} GB/s")
 
     # dominant kernel, one launch at a time
-    if plan.path == 2 and not bf16:
+    if plan.path == 2 and fmt == "f32":
         pairs = torch.empty(2 * rows, dtype=torch.float32, device="cuda")
         B.softmax2p_f32_pass1(xs[0], pairs, rows, n)
         p1 = per_launch_ms(torch, lambda i: B.softmax2p_f32_pass1(xs[i], pairs, rows, n), steps, sets)
@@ -156,7 +159,7 @@ def run_workload(torch, B, W, name, steps, warmup, full):
         variants[0][1](xs[0], ys[0], rows, n)
         torch.cuda.synchronize()
         y_host = ys[0].cpu().numpy()
-        if bf16:
+        if s == 2:
             y_host = y_host.view(np.uint16)
         y_host = y_host.reshape(rows, n)
     del xs, ys
@@ -296,7 +299,7 @@ def main():
     if not args.quick:
         result["calibration"] = calibration(torch, B, args.steps, args.warmup)
         others = {}
-        for name in ("cfg2", "cfg3", "cfg4", "cfg5"):
+        for name in ("cfg2", "cfg3", "cfg4", "cfg5", "cfg5_f16"):
             if name == args.workload:
                 continue
             o, _, _ = run_workload(torch, B, W, name, args.steps, args.warmup, False)

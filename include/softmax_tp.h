@@ -92,10 +92,27 @@ TP_API int softmax3p_reload_bf16io(const uint16_t *x, uint16_t *y, int64_t rows,
                                    void *stream);
 
 /*
+ * Algorithms 3, 1 and 2 with IEEE binary16 storage: x and y hold fp16 bit patterns, widened
+ * to fp32 exactly (subnormal inputs included) and rounded to fp16 (nearest even) on the
+ * way out; the arithmetic between is the fp32 one of the *_f32 entry points.  Not in the
+ * paper, which is fp32 only (Section 6.3).  fp16 has 11 significand bits and a narrow
+ * exponent range: results below 2^-14 come out as fp16 subnormals (absolute error at most
+ * 2^-25) and results below 2^-25 as zero, which is where this format stops being useful
+ * for rows of many millions of comparable elements.  Target accuracy against the unrounded
+ * result: 5e-4 relative for results of at least 2^-14 (1.1e-3 for the reloading variant,
+ * whose y holds Exp(x - mu) rounded to fp16 between its second and third pass).
+ */
+TP_API int softmax2p_f16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n, void *stream);
+TP_API int softmax3p_recompute_f16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n,
+                                     void *stream);
+TP_API int softmax3p_reload_f16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n,
+                                  void *stream);
+
+/*
  * On-chip variant of Algorithm 3 for short rows (n <= TP_ONCHIP_MAX_N): a workgroup
  * loads a row into registers, runs pass 1 and pass 2 on the registers and writes y, while
  * the loads of its next row are already in flight.  Same arithmetic and results as
- * softmax2p_f32 / softmax2p_bf16io up to summation order, but x is read from memory only
+ * softmax2p_f32 / _bf16io / _f16io up to summation order, but x is read from memory only
  * once (2 N elements of traffic instead of 3 N): the regime in which, as the paper notes
  * (Sections 6.4 and 7), the Two-Pass algorithm has no bandwidth advantage left to offer.
  * Kept as an entry point of its own so that its throughput is never mistaken for the
@@ -106,6 +123,8 @@ TP_API int softmax3p_reload_bf16io(const uint16_t *x, uint16_t *y, int64_t rows,
 TP_API int softmax2p_onchip_f32(const float *x, float *y, int64_t rows, int64_t n, void *stream);
 TP_API int softmax2p_onchip_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n,
                                    void *stream);
+TP_API int softmax2p_onchip_f16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n,
+                                  void *stream);
 
 /*
  * The same on-chip arrangement for Algorithm 2 (Section 3): max, Exp(x - mu) held in
@@ -117,6 +136,8 @@ TP_API int softmax2p_onchip_bf16io(const uint16_t *x, uint16_t *y, int64_t rows,
 TP_API int softmax3p_onchip_f32(const float *x, float *y, int64_t rows, int64_t n, void *stream);
 TP_API int softmax3p_onchip_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n,
                                    void *stream);
+TP_API int softmax3p_onchip_f16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n,
+                                  void *stream);
 
 /* ----- pieces of the path, exported for tests and for per-pass timing ----- */
 

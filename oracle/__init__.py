@@ -69,13 +69,13 @@ def lib():
         build()
         L = ctypes.CDLL(_LIB_PATH)
         L.oracle_threads_available.restype = ctypes.c_int
-        for name in ("oracle_stats_f32", "oracle_stats_bf16"):
+        for name in ("oracle_stats_f32", "oracle_stats_bf16", "oracle_stats_f16"):
             getattr(L, name).argtypes = [_vp, _i64, _i64, _vp, _vp, ctypes.c_int]
             getattr(L, name).restype = None
-        for name in ("oracle_softmax_f32", "oracle_softmax_bf16"):
+        for name in ("oracle_softmax_f32", "oracle_softmax_bf16", "oracle_softmax_f16"):
             getattr(L, name).argtypes = [_vp, _i64, _i64, _vp, ctypes.c_int]
             getattr(L, name).restype = None
-        for name in ("oracle_compare_f32", "oracle_compare_bf16"):
+        for name in ("oracle_compare_f32", "oracle_compare_bf16", "oracle_compare_f16"):
             getattr(L, name).argtypes = [_vp, _vp, _i64, _i64, ctypes.c_double,
                                          ctypes.POINTER(Cmp), ctypes.c_int]
             getattr(L, name).restype = None
@@ -111,37 +111,42 @@ def _ptr(a):
     return a.ctypes.data_as(_vp)
 
 
-def stats(x, bf16: bool = False, threads: int = 0):
-    """Per-row (mu, S) as numpy longdouble arrays.  x: fp32 values or bf16 bit patterns."""
-    a = _as2d(x, np.uint16 if bf16 else np.float32)
+def _kind(bf16, f16):
+    assert not (bf16 and f16)
+    return "bf16" if bf16 else "f16" if f16 else "f32"
+
+
+def stats(x, bf16: bool = False, threads: int = 0, f16: bool = False):
+    """Per-row (mu, S) as numpy longdouble arrays.  x: fp32 values, or bf16 / fp16 bit patterns."""
+    a = _as2d(x, np.uint16 if (bf16 or f16) else np.float32)
     rows, n = a.shape
     mu = np.zeros(rows, dtype=np.longdouble)
     S = np.zeros(rows, dtype=np.longdouble)
-    fn = lib().oracle_stats_bf16 if bf16 else lib().oracle_stats_f32
+    fn = getattr(lib(), "oracle_stats_" + _kind(bf16, f16))
     fn(_ptr(a), rows, n, _ptr(mu), _ptr(S), threads)
     return mu, S
 
 
-def softmax(x, bf16: bool = False, threads: int = 0):
+def softmax(x, bf16: bool = False, threads: int = 0, f16: bool = False):
     """Row-wise softmax as a numpy longdouble array of x's shape."""
     shape = np.shape(x)
-    a = _as2d(x, np.uint16 if bf16 else np.float32)
+    a = _as2d(x, np.uint16 if (bf16 or f16) else np.float32)
     rows, n = a.shape
     p = np.zeros((rows, n), dtype=np.longdouble)
-    fn = lib().oracle_softmax_bf16 if bf16 else lib().oracle_softmax_f32
+    fn = getattr(lib(), "oracle_softmax_" + _kind(bf16, f16))
     fn(_ptr(a), rows, n, _ptr(p), threads)
     return p.reshape(shape)
 
 
-def compare(x, y, tol: float, bf16: bool = False, threads: int = 0) -> Cmp:
+def compare(x, y, tol: float, bf16: bool = False, threads: int = 0, f16: bool = False) -> Cmp:
     """Stream y against the oracle's p for x (same shape); see oracle_cmp_t."""
-    dt = np.uint16 if bf16 else np.float32
+    dt = np.uint16 if (bf16 or f16) else np.float32
     a = _as2d(x, dt)
     b = _as2d(y, dt)
     assert a.shape == b.shape
     rows, n = a.shape
     out = Cmp()
-    fn = lib().oracle_compare_bf16 if bf16 else lib().oracle_compare_f32
+    fn = getattr(lib(), "oracle_compare_" + _kind(bf16, f16))
     fn(_ptr(a), _ptr(b), rows, n, float(tol), ctypes.byref(out), threads)
     return out
 

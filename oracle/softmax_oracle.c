@@ -44,7 +44,7 @@ _Static_assert(LDBL_MANT_DIG >= 64, "the oracle needs a long double with a 64-bi
 /* element decoding                                                    */
 /* ------------------------------------------------------------------ */
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2 };
 
 /* bfloat16 is the upper half of an IEEE binary32: same sign and exponent, 7
  * explicit significand bits.  Every bf16 value is exactly a binary32 value. */
@@ -56,11 +56,40 @@ static long double decode_bf16(uint16_t h)
     return (long double)f;
 }
 
+/* IEEE 754 binary16: 1 sign bit, 5 exponent bits (bias 15), 10 fraction bits;
+ * exponent field 0 holds the subnormals f * 2^-24, exponent field 31 infinities and NaNs. */
+static long double decode_f16(uint16_t h)
+{
+    const int sign = h >> 15, e = (h >> 10) & 31, f = h & 1023;
+    long double v;
+    if (e == 0)
+        v = ldexpl((long double)f, -24);
+    else if (e == 31)
+        v = f ? (long double)NAN : (long double)INFINITY;
+    else
+        v = ldexpl((long double)(1024 + f), e - 25);
+    return sign ? -v : v;
+}
+
 static long double elem_at(const void *base, int kind, int64_t idx)
 {
     if (kind == ORACLE_F32)
         return (long double)((const float *)base)[idx];
+    if (kind == ORACLE_F16)
+        return decode_f16(((const uint16_t *)base)[idx]);
     return decode_bf16(((const uint16_t *)base)[idx]);
+}
+
+/* Smallest normal number of the output format: below it a result may be flushed to zero. */
+static long double min_normal(int kind)
+{
+    return kind == ORACLE_F16 ? ldexpl(1.0L, -14) : (long double)FLT_MIN;
+}
+
+/* Largest finite number of the output format. */
+static long double max_finite(int kind)
+{
+    return kind == ORACLE_F16 ? 65504.0L : (long double)FLT_MAX;
 }
 
 static long double out_at(const void *base, int kind, int64_t idx)
@@ -318,10 +347,12 @@ void oracle_prob_at_f32(const float *x, int64_t row_off, const int64_t *idx, int
 /*
  * Compares a candidate output y against p without storing p.
  *
- *   p_i >= FLT_MIN : rel_i = |y_i - p_i| / p_i, violation if rel_i > tol
- *   p_i <  FLT_MIN : abs_i = |y_i - p_i|, violation if abs_i > FLT_MIN
- *                    (the paper allows subnormal results to be flushed to
- *                     zero, Section 6.3, so either 0 or the denormal passes)
+ *   p_i >= TINY : rel_i = |y_i - p_i| / p_i, violation if rel_i > tol
+ *   p_i <  TINY : abs_i = |y_i - p_i|, violation if abs_i > TINY
+ *                 (the paper allows subnormal results to be flushed to
+ *                  zero, Section 6.3, so either 0 or the denormal passes)
+ *   TINY is the smallest normal number of the storage format of y: FLT_MIN for
+ *   fp32 and bf16 (same exponent range), 2^-14 for fp16.
  *   any y_i that is NaN, infinite or negative is counted separately.
  *   row sums of y are accumulated in long double.
  */
@@ -357,17 +388,19 @@ static void cmp_init(oracle_cmp_t *c)
     c->worst_index = -1;
 }
 
-static void cmp_elem(oracle_cmp_t *acc, long double p, long double y, double tol, int64_t flat)
+static void cmp_elem(oracle_cmp_t *acc, long double p, long double y, double tol, int64_t flat,
+                     int kind)
 {
+    const long double tiny = min_normal(kind);
     acc->n_total++;
-    if (!(y == y) || y > (long double)FLT_MAX || y < -(long double)FLT_MAX) {
+    if (!(y == y) || y > max_finite(kind) || y < -max_finite(kind)) {
         acc->n_nonfinite++;
         return;
     }
     if (y < 0.0L)
         acc->n_negative++;
     long double d = fabsl(y - p);
-    if (p >= (long double)FLT_MIN) {
+    if (p >= tiny) {
         acc->n_normal++;
         double rel = (double)(d / p);
         if (rel > acc->max_rel_err) {
@@ -381,7 +414,7 @@ static void cmp_elem(oracle_cmp_t *acc, long double p, long double y, double tol
     } else {
         if ((double)d > acc->max_sub_abs_err)
             acc->max_sub_abs_err = (double)d;
-        if (d > (long double)FLT_MIN)
+        if (d > tiny)
             acc->n_sub_viol++;
     }
 }
@@ -417,7 +450,7 @@ static void cmp_rows(void *c, int tid, int64_t lo, int64_t hi)
             int64_t k = r * q->n + i;
             long double p = expl(elem_at(q->x, q->kind, k) - q->mu[r]) / q->S[r];
             long double y = out_at(q->y, q->kind, k);
-            cmp_elem(acc, p, y, q->tol, k);
+            cmp_elem(acc, p, y, q->tol, k, q->kind);
             if (y == y)
                 rowsum += y;
         }
@@ -438,7 +471,7 @@ static void cmp_one_row_range(void *c, int tid, int64_t lo, int64_t hi)
         int64_t k = r * q->n + i;
         long double p = expl(elem_at(q->x, q->kind, k) - q->mu[r]) / q->S[r];
         long double y = out_at(q->y, q->kind, k);
-        cmp_elem(acc, p, y, q->tol, k);
+        cmp_elem(acc, p, y, q->tol, k, q->kind);
         if (y == y)
             rowsum += y;
     }
@@ -499,6 +532,24 @@ void oracle_compare_bf16(const uint16_t *x, const uint16_t *y, int64_t rows, int
                          oracle_cmp_t *out, int threads)
 {
     compare_any(x, y, ORACLE_BF16, rows, n, tol, out, threads);
+}
+
+/* x and y are both IEEE binary16 bit patterns; y is compared with the unrounded p. */
+void oracle_compare_f16(const uint16_t *x, const uint16_t *y, int64_t rows, int64_t n, double tol,
+                        oracle_cmp_t *out, int threads)
+{
+    compare_any(x, y, ORACLE_F16, rows, n, tol, out, threads);
+}
+
+void oracle_stats_f16(const uint16_t *x, int64_t rows, int64_t n, long double *mu, long double *S,
+                      int threads)
+{
+    stats_any(x, ORACLE_F16, rows, n, mu, S, threads);
+}
+
+void oracle_softmax_f16(const uint16_t *x, int64_t rows, int64_t n, long double *p, int threads)
+{
+    softmax_any(x, ORACLE_F16, rows, n, p, threads);
 }
 
 /* ------------------------------------------------------------------ */

@@ -25,10 +25,15 @@ ENTRY_POINTS = {
     "softmax2p_bf16io": [_vp, _vp, _i64, _i64, _vp],
     "softmax3p_recompute_bf16io": [_vp, _vp, _i64, _i64, _vp],
     "softmax3p_reload_bf16io": [_vp, _vp, _i64, _i64, _vp],
+    "softmax2p_f16io": [_vp, _vp, _i64, _i64, _vp],
+    "softmax3p_recompute_f16io": [_vp, _vp, _i64, _i64, _vp],
+    "softmax3p_reload_f16io": [_vp, _vp, _i64, _i64, _vp],
     "softmax2p_onchip_f32": [_vp, _vp, _i64, _i64, _vp],
     "softmax2p_onchip_bf16io": [_vp, _vp, _i64, _i64, _vp],
+    "softmax2p_onchip_f16io": [_vp, _vp, _i64, _i64, _vp],
     "softmax3p_onchip_f32": [_vp, _vp, _i64, _i64, _vp],
     "softmax3p_onchip_bf16io": [_vp, _vp, _i64, _i64, _vp],
+    "softmax3p_onchip_f16io": [_vp, _vp, _i64, _i64, _vp],
     "softmax_tp_extexp_f32": [_vp, _vp, _vp, _i64, _vp],
     "softmax2p_f32_pass1": [_vp, _vp, _i64, _i64, _vp],
     "softmax2p_f32_pass2": [_vp, _vp, _vp, _i64, _i64, _vp],
@@ -169,6 +174,18 @@ def softmax3p_reload_bf16io(x, y, rows, n, stream=None):
     _softmax("softmax3p_reload_bf16io", x, y, rows, n, stream)
 
 
+def softmax2p_f16io(x, y, rows, n, stream=None):
+    _softmax("softmax2p_f16io", x, y, rows, n, stream)
+
+
+def softmax3p_recompute_f16io(x, y, rows, n, stream=None):
+    _softmax("softmax3p_recompute_f16io", x, y, rows, n, stream)
+
+
+def softmax3p_reload_f16io(x, y, rows, n, stream=None):
+    _softmax("softmax3p_reload_f16io", x, y, rows, n, stream)
+
+
 def softmax2p_onchip_f32(x, y, rows, n, stream=None):
     _softmax("softmax2p_onchip_f32", x, y, rows, n, stream)
 
@@ -177,12 +194,20 @@ def softmax2p_onchip_bf16io(x, y, rows, n, stream=None):
     _softmax("softmax2p_onchip_bf16io", x, y, rows, n, stream)
 
 
+def softmax2p_onchip_f16io(x, y, rows, n, stream=None):
+    _softmax("softmax2p_onchip_f16io", x, y, rows, n, stream)
+
+
 def softmax3p_onchip_f32(x, y, rows, n, stream=None):
     _softmax("softmax3p_onchip_f32", x, y, rows, n, stream)
 
 
 def softmax3p_onchip_bf16io(x, y, rows, n, stream=None):
     _softmax("softmax3p_onchip_bf16io", x, y, rows, n, stream)
+
+
+def softmax3p_onchip_f16io(x, y, rows, n, stream=None):
+    _softmax("softmax3p_onchip_f16io", x, y, rows, n, stream)
 
 
 def softmax_tp_extexp_f32(x, m, e, count, stream=None):

@@ -59,8 +59,8 @@ static void rows_shape(int64_t nvec, int elem_bytes, softmax_tp_shape_t *s)
         return;
     }
     static const int cand_f32[][2] = {{1024, 8}, {1024, 4}, {512, 4}, {512, 2}, {256, 2}};
-    static const int cand_bf16[][2] = {{1024, 4}, {1024, 2}, {512, 2}, {256, 2}, {256, 2}};
-    const int(*cand)[2] = elem_bytes == 4 ? cand_f32 : cand_bf16;
+    static const int cand_16bit[][2] = {{1024, 4}, {1024, 2}, {512, 2}, {256, 2}, {256, 2}};
+    const int(*cand)[2] = elem_bytes == 4 ? cand_f32 : cand_16bit;
     s->block = cand[4][0];
     s->unroll = cand[4][1];
     for (int i = 0; i < 5; ++i) {
@@ -251,9 +251,9 @@ static bool pass_reversed(int k) { return g_tune.direction == 1 ? false : (k & 1
 template <int N>
 using ic = std::integral_constant<int, N>;
 
-// Calls f(ic<BLOCK>, ic<U>) for the shape's block and unroll.  bf16 vectors unpack to 8
+// Calls f(ic<BLOCK>, ic<U>) for the shape's block and unroll.  16-bit vectors unpack to 8
 // floats each, so 8 of them in flight would not fit the registers of a 1024-thread
-// workgroup: the bf16 formats stop at 4.
+// workgroup: the 16-bit formats stop at 4.
 template <class IO, class F>
 static int with_shape(const softmax_tp_shape_t &s, F &&f)
 {
@@ -685,6 +685,22 @@ int softmax3p_reload_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_
     return softmax_any<BF16x8, BF16x1>(kReload, x, y, rows, n, stream);
 }
 
+int softmax2p_f16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n, void *stream)
+{
+    return softmax_any<F16x8, F16x1>(kTwoPass, x, y, rows, n, stream);
+}
+
+int softmax3p_recompute_f16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n,
+                              void *stream)
+{
+    return softmax_any<F16x8, F16x1>(kRecompute, x, y, rows, n, stream);
+}
+
+int softmax3p_reload_f16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n, void *stream)
+{
+    return softmax_any<F16x8, F16x1>(kReload, x, y, rows, n, stream);
+}
+
 int softmax2p_onchip_f32(const float *x, float *y, int64_t rows, int64_t n, void *stream)
 {
     return run_onchip<F32x4>(kOnchipTwoPass, x, y, rows, n, stream);
@@ -693,6 +709,16 @@ int softmax2p_onchip_f32(const float *x, float *y, int64_t rows, int64_t n, void
 int softmax2p_onchip_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n, void *stream)
 {
     return run_onchip<BF16x8>(kOnchipTwoPass, x, y, rows, n, stream);
+}
+
+int softmax2p_onchip_f16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n, void *stream)
+{
+    return run_onchip<F16x8>(kOnchipTwoPass, x, y, rows, n, stream);
+}
+
+int softmax3p_onchip_f16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n, void *stream)
+{
+    return run_onchip<F16x8>(kOnchipThreePass, x, y, rows, n, stream);
 }
 
 int softmax3p_onchip_f32(const float *x, float *y, int64_t rows, int64_t n, void *stream)

@@ -17,6 +17,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kWave = 64;
 constexpr int kMaxWaves = 16;
@@ -273,6 +274,65 @@ struct BF16x1 {  // bf16, element-wise
     }
     static __device__ __forceinline__ float load1(const elem *p) { return BF16x8::load1(p); }
     static __device__ __forceinline__ void store1(elem *p, float v) { BF16x8::store1(p, v); }
+    static __device__ __forceinline__ vec zero() { return 0; }
+};
+
+// IEEE binary16 widens to fp32 exactly (its subnormals too: the conversion instructions
+// honour them in the default floating-point mode) and narrows with round to nearest even.
+__device__ __forceinline__ void f16_unpack(uint32_t w, float &lo, float &hi)
+{
+    const f32x2 p = __builtin_convertvector(__builtin_bit_cast(f16x2, w), f32x2);
+    lo = p.x;
+    hi = p.y;
+}
+__device__ __forceinline__ uint32_t f16_pack(float lo, float hi)
+{
+    f32x2 p = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(p, f16x2));
+}
+
+struct F16x8 {  // fp16 in and out, 16-byte vectors, fp32 arithmetic
+    using elem = uint16_t;
+    using vec = u32x4;
+    static constexpr int V = 8;
+    static __device__ __forceinline__ void unpack(vec v, float *o)
+    {
+        f16_unpack(v.x, o[0], o[1]);
+        f16_unpack(v.y, o[2], o[3]);
+        f16_unpack(v.z, o[4], o[5]);
+        f16_unpack(v.w, o[6], o[7]);
+    }
+    static __device__ __forceinline__ vec pack(const float *o)
+    {
+        vec v = {f16_pack(o[0], o[1]), f16_pack(o[2], o[3]), f16_pack(o[4], o[5]),
+                 f16_pack(o[6], o[7])};
+        return v;
+    }
+    static __device__ __forceinline__ float load1(const elem *p)
+    {
+        return (float)__builtin_bit_cast(_Float16, *p);
+    }
+    static __device__ __forceinline__ void store1(elem *p, float v)
+    {
+        *p = __builtin_bit_cast(uint16_t, (_Float16)v);
+    }
+    static __device__ __forceinline__ vec zero() { vec v = {0u, 0u, 0u, 0u}; return v; }
+};
+
+struct F16x1 {  // fp16, element-wise
+    using elem = uint16_t;
+    using vec = uint16_t;
+    static constexpr int V = 1;
+    static __device__ __forceinline__ void unpack(vec v, float *o)
+    {
+        o[0] = (float)__builtin_bit_cast(_Float16, v);
+    }
+    static __device__ __forceinline__ vec pack(const float *o)
+    {
+        return __builtin_bit_cast(uint16_t, (_Float16)o[0]);
+    }
+    static __device__ __forceinline__ float load1(const elem *p) { return F16x8::load1(p); }
+    static __device__ __forceinline__ void store1(elem *p, float v) { F16x8::store1(p, v); }
     static __device__ __forceinline__ vec zero() { return 0; }
 };
 

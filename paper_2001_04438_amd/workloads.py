@@ -51,6 +51,17 @@ def bf16_bits_to_f32(h: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(h, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
 
 
+def f32_to_f16_bits(a: np.ndarray) -> np.ndarray:
+    """Round fp32 to IEEE binary16 (round-to-nearest-even), returned as uint16 bit patterns."""
+    with np.errstate(over="ignore"):
+        return np.ascontiguousarray(a, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def f16_bits_to_f32(h: np.ndarray) -> np.ndarray:
+    """Widen binary16 bit patterns to the fp32 values they denote (exact)."""
+    return np.ascontiguousarray(h, dtype=np.uint16).view(np.float16).astype(np.float32)
+
+
 def _rng(cfg_index: int) -> np.random.Generator:
     return np.random.Generator(np.random.PCG64(BASE_SEED + cfg_index))
 

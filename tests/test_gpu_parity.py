@@ -7,8 +7,13 @@ compare element by element with the oracle's streaming comparator:
   bf16 I/O, Two-Pass     |y - p| <= 1e-2 p      (p is the unrounded long-double value)
   fp32 I/O, Three-Pass   |y - p| <= 1e-5 p      (the fp32 subtraction x - mu alone costs up to
                                                  2^-24 |x - mu| <= 5.2e-6 while p >= FLT_MIN)
-  p < FLT_MIN            |y - p| <= FLT_MIN     (flushed zero or denormal both pass)
-  every y finite, >= 0;  |sum_i y_i - 1| <= tol + n 2^-126
+  fp16 I/O               |y - p| <= 5e-4 p      where p >= 2^-14: one rounding to 11 bits (2^-11 =
+                                                 4.883e-4) on top of the fp32 result; 1.1e-3 for
+                                                 the reloading variant, which rounds twice
+  p < FLT_MIN            |y - p| <= FLT_MIN     (flushed zero or denormal both pass; for fp16 I/O
+                                                 the threshold is the format's 2^-14)
+  every y finite, >= 0;  |sum_i y_i - 1| <= tol + n 2^-126   (fp16: + n 2^-25, the rounding of
+                                                 results in the subnormal range)
 """
 import math
 
@@ -22,6 +27,8 @@ pytestmark = pytest.mark.gpu
 TOL_2P = 4e-6
 TOL_3P = 1e-5
 TOL_BF16 = 1e-2
+TOL_F16 = 5e-4
+TOL_F16_RELOAD = 1.1e-3
 
 
 @pytest.fixture(scope="module")
@@ -63,17 +70,28 @@ def _run(fn, x, inplace=False, x_off=0, y_off=0):
     return y.reshape(rows, n)
 
 
-def _check(oracle_mod, x, y, tol, bf16=False):
-    c = oracle_mod.compare(x, y, tol, bf16=bf16)
+def _check(oracle_mod, x, y, tol, bf16=False, f16=False):
+    c = oracle_mod.compare(x, y, tol, bf16=bf16, f16=f16)
     n = x.shape[1]
     assert c.n_total == x.size
     assert c.ok(), c.as_dict()
-    assert c.max_row_sum_dev <= (tol if not bf16 else 2 * tol) + n * 2.0 ** -126, c.as_dict()
+    if f16:
+        assert c.max_row_sum_dev <= 2 * tol + n * 2.0 ** -25, c.as_dict()
+    else:
+        assert c.max_row_sum_dev <= (tol if not bf16 else 2 * tol) + n * 2.0 ** -126, c.as_dict()
     return c
 
 
 ALGOS_F32 = [("softmax2p_f32", TOL_2P), ("softmax3p_recompute_f32", TOL_3P),
              ("softmax3p_reload_f32", TOL_3P)]
+ALGOS_F16 = [("softmax2p_f16io", TOL_F16), ("softmax3p_recompute_f16io", TOL_F16),
+             ("softmax3p_reload_f16io", TOL_F16_RELOAD)]
+ONCHIP_F16 = [("softmax2p_onchip_f16io", TOL_F16), ("softmax3p_onchip_f16io", TOL_F16)]
+
+
+def _f16(rng, rows, n, scale, shift=0.0):
+    x = rng.standard_normal((rows, n)) * scale + shift
+    return workloads.f32_to_f16_bits(x.astype(np.float32)).reshape(rows, n)
 
 
 # ---------------------------------------------------------------------------
@@ -219,6 +237,57 @@ def test_in_place(gpu, oracle_mod, name, tol):
 def test_in_place_bf16(gpu, oracle_mod):
     x = workloads.cfg5(rows=9, n=3001)
     _check(oracle_mod, x, _run(gpu.softmax2p_bf16io, x, inplace=True), TOL_BF16, bf16=True)
+
+
+# ---------------------------------------------------------------------------
+# fp16 storage
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name,tol", ALGOS_F16 + ONCHIP_F16)
+def test_f16_all_paths(gpu, oracle_mod, name, tol):
+    rng = np.random.default_rng(1616)
+    fn = getattr(gpu, name)
+    onchip = "onchip" in name
+    shapes = [(1000, 300, 2.0), (257, 1000, 1.0), (64, 4096, 2.0), (5, 21846, 4.0), (3, 32768, 6.0)]
+    if not onchip:
+        shapes += [(40, 65536, 6.0), (2, 300_001, 8.0), (1, 1 << 21, 10.0)]
+    normal = 0
+    for rows, n, scale in shapes:
+        x = _f16(rng, rows, n, scale, shift=rng.uniform(-30, 30, size=(rows, 1)))
+        c = _check(oracle_mod, x, _run(fn, x), tol, f16=True)
+        normal += c.n_normal
+    assert normal > 400_000          # enough results in the normal range for the relative bound to bite
+    x = _f16(rng, 7, 5003, 3.0)
+    _check(oracle_mod, x, _run(fn, x, x_off=3, y_off=3), tol, f16=True)
+    _check(oracle_mod, x, _run(fn, x, inplace=True), tol, f16=True)
+    if not onchip:                   # x and y not congruent modulo 16 bytes: element-wise kernels
+        _check(oracle_mod, x, _run(fn, x, x_off=1, y_off=2), tol, f16=True)
+        x = _f16(rng, 2, 200_003, 8.0)
+        _check(oracle_mod, x, _run(fn, x, x_off=1, y_off=4), tol, f16=True)
+
+
+@pytest.mark.parametrize("name,tol", ALGOS_F16)
+def test_f16_edge_lengths_and_range(gpu, oracle_mod, name, tol):
+    rng = np.random.default_rng(1617)
+    fn = getattr(gpu, name)
+    for rows in (1, 3):
+        for n in (1, 2, 7, 8, 9, 63, 64, 65, 511, 513, 2047, 2049, 8191, 8193):
+            x = _f16(rng, rows, n, 5.0)
+            _check(oracle_mod, x, _run(fn, x), tol, f16=True)
+    # the whole range of the format in one row: +-65504 next to subnormals and zeros
+    x = np.array([[0x7BFF, 0xFBFF, 0x0001, 0x8001, 0x03FF, 0x0000, 0x8000, 0x7BFE, 0x7BFF, 0x3C00]],
+                 dtype=np.uint16)
+    y = _run(fn, x)
+    c = _check(oracle_mod, x, y, tol, f16=True)
+    assert c.n_normal == 2           # the two maxima share the mass; their neighbour is 32 below
+    # rows made of fp16 subnormals and zeros only: a uniform distribution to within 6e-5
+    x = rng.integers(0, 0x0400, size=(4, 1000)).astype(np.uint16)
+    x[:, ::3] |= 0x8000
+    _check(oracle_mod, x, _run(fn, x), tol, f16=True)
+    # a long flat row: every result is an fp16 subnormal, held to 2^-25 absolute
+    x = _f16(rng, 1, 1 << 20, 0.01)
+    c = _check(oracle_mod, x, _run(fn, x), tol, f16=True)
+    assert c.n_normal == 0 and c.max_sub_abs_err <= 2.0 ** -25 * 1.01
 
 
 def test_empty_and_invalid_arguments(gpu):
@@ -453,6 +522,7 @@ def test_random_shapes_all_entry_points(gpu, oracle_mod):
            ("softmax2p_onchip_f32", TOL_2P), ("softmax3p_onchip_f32", TOL_3P)]
     bf16 = ["softmax2p_bf16io", "softmax3p_recompute_bf16io", "softmax3p_reload_bf16io",
             "softmax2p_onchip_bf16io", "softmax3p_onchip_bf16io"]
+    f16 = ALGOS_F16 + ONCHIP_F16
     for trial in range(40):
         kind = trial % 4
         if kind == 0:      # short rows, many of them
@@ -468,6 +538,7 @@ def test_random_shapes_all_entry_points(gpu, oracle_mod):
         scale = float(rng.choice([0.5, 4.0, 30.0]))
         x = (rng.standard_normal((rows, n)) * scale + rng.uniform(-50, 50, size=(rows, 1))).astype(np.float32)
         xb = workloads.f32_to_bf16_bits(x).reshape(rows, n)
+        xh = workloads.f32_to_f16_bits(x).reshape(rows, n)
         print(f"trial {trial}: rows={rows} n={n} off={off} scale={scale}", flush=True)
         for name, tol in f32:
             if "onchip" in name and n > 32768:
@@ -477,6 +548,10 @@ def test_random_shapes_all_entry_points(gpu, oracle_mod):
             if "onchip" in name and n > 32768:
                 continue
             _check(oracle_mod, xb, _run(getattr(gpu, name), xb, x_off=2 * off, y_off=2 * off), TOL_BF16, bf16=True)
+        for name, tol in f16:
+            if "onchip" in name and n > 32768:
+                continue
+            _check(oracle_mod, xh, _run(getattr(gpu, name), xh, x_off=2 * off, y_off=2 * off), tol, f16=True)
 
 
 def test_reserve_and_release(gpu, oracle_mod):

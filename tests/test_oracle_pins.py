@@ -279,6 +279,31 @@ def test_bf16_bit_patterns(oracle_mod):
     assert np.array_equal(p5, oracle_mod.softmax(workloads.bf16_bits_to_f32(x5)))
 
 
+def test_f16_decoding_exhaustive(oracle_mod):
+    # IEEE binary16: sign | 5 exponent bits (bias 15) | 10 fraction bits.  Values written out by hand
+    bits = np.array([0x3C00, 0xC000, 0x0000, 0x7BFF, 0x0001, 0x03FF, 0x0400, 0x3555, 0xFBFF],
+                    dtype=np.uint16)
+    want = [1.0, -2.0, 0.0, 65504.0, 2.0 ** -24, 1023 * 2.0 ** -24, 2.0 ** -14,
+            (1024 + 0x155) * 2.0 ** -12, -65504.0]
+    mu, S = oracle_mod.stats(bits.reshape(-1, 1), f16=True)   # a row of one element: mu is the element
+    assert [float(v) for v in mu] == want and np.all(S == 1)
+    # every finite pattern against numpy's half type (an independent implementation of the format)
+    allbits = np.arange(1 << 16, dtype=np.uint16)
+    finite = allbits[(allbits & 0x7C00) != 0x7C00]
+    mu, _ = oracle_mod.stats(finite.reshape(-1, 1), f16=True)
+    assert np.array_equal(mu.astype(np.float64), finite.view(np.float16).astype(np.float64))
+    assert finite.size == 2 * 31 * 1024
+    # the generators' rounding on the way in: nearest even at 11 significand bits
+    f = np.array([1.0, 1 + 2.0 ** -11, 1 + 3 * 2.0 ** -11, 1 + 2.0 ** -11 + 2.0 ** -20, 65519.0, 3e-8],
+                 dtype=np.float32)
+    assert list(workloads.f32_to_f16_bits(f)) == [0x3C00, 0x3C00, 0x3C02, 0x3C01, 0x7BFF, 0x0001]
+    assert np.array_equal(workloads.f16_bits_to_f32(bits), np.array(want, dtype=np.float32))
+    # a softmax over fp16 bit patterns is the softmax of the values they denote
+    x = workloads.f32_to_f16_bits(np.random.default_rng(5).normal(0, 3, (2, 777)).astype(np.float32))
+    assert np.array_equal(oracle_mod.softmax(x, f16=True),
+                          oracle_mod.softmax(workloads.f16_bits_to_f32(x)))
+
+
 # --------------------------------------------------------------------------
 # fp32 thresholds printed in the paper (negative control for the probes)
 # --------------------------------------------------------------------------
@@ -365,6 +390,39 @@ def test_comparator_bf16(oracle_mod):
     assert abs(c1.max_row_sum_dev - c8.max_row_sum_dev) < 1e-15
 
 
+def test_comparator_f16(oracle_mod):
+    rng = np.random.default_rng(16)
+    x = workloads.f32_to_f16_bits(rng.normal(0, 2, (4, 1001)).astype(np.float32))
+    p = oracle_mod.softmax(x, f16=True)
+    y = workloads.f32_to_f16_bits(p.astype(np.float32))
+    c = oracle_mod.compare(x, y, 5e-4, f16=True)
+    assert c.ok() and c.n_total == x.size
+    assert 2.0 ** -13 < c.max_rel_err <= 2.0 ** -11 * 1.0001        # one rounding to 11 bits
+    assert 0 < c.n_normal < c.n_total                                # some results are fp16 subnormals
+    assert c.max_sub_abs_err <= 2.0 ** -25 * 1.0001
+    # two ulps off on a normal result is a violation at 5e-4
+    k = int(np.argmax(p[2]))
+    y2 = y.copy()
+    y2[2, k] += 2
+    c2 = oracle_mod.compare(x, y2, 5e-4, f16=True)
+    assert c2.n_rel_viol == 1 and c2.worst_index == 2 * 1001 + k
+    # the flush-to-zero allowance starts at the format's own smallest normal, 2^-14, not at fp32's
+    for a, normal in ((9.625, True), (9.75, False)):
+        xa = workloads.f32_to_f16_bits(np.array([[0.0, -a]], dtype=np.float32))
+        pa = oracle_mod.softmax(xa, f16=True)[0]
+        assert (pa[1] >= 2.0 ** -14) == normal
+        y0 = np.array([[0x3C00, 0x0000]], dtype=np.uint16)           # [1.0, flushed to zero]
+        ca = oracle_mod.compare(xa, y0, 5e-4, f16=True)
+        assert (ca.n_rel_viol == 1) == normal and ca.n_sub_viol == 0
+    # infinities and NaNs of the format are counted
+    y3 = y.copy()
+    y3[0, 0] = 0x7C00
+    y3[0, 1] = 0x7E00
+    y3[1, 0] |= 0x8000
+    c3 = oracle_mod.compare(x, y3, 5e-4, f16=True)
+    assert c3.n_nonfinite == 2 and c3.n_negative == 1
+
+
 # --------------------------------------------------------------------------
 # the oracle's C code under the address and undefined-behaviour sanitizers
 # --------------------------------------------------------------------------
@@ -396,6 +454,11 @@ for rows, n, threads in ((1, 1, 1), (3, 17, 2), (2, 4099, 8), (1, 100003, 5), (7
     h = (x.view(np.uint32) >> 16).astype(np.uint16)
     L.oracle_softmax_bf16(h.ctypes.data_as(vp), i64(rows), i64(n), p.ctypes.data_as(vp), threads)
     assert abs(float(p.sum()) - rows) < 1e-9
+    g = x.astype(np.float16).view(np.uint16)
+    L.oracle_softmax_f16(g.ctypes.data_as(vp), i64(rows), i64(n), p.ctypes.data_as(vp), threads)
+    assert abs(float(p.sum()) - rows) < 1e-9
+    L.oracle_compare_f16(g.ctypes.data_as(vp), g.ctypes.data_as(vp), i64(rows), i64(n),
+                         ctypes.c_double(5e-4), buf, threads)
 d = np.linspace(-50, 50, 1001)
 yd = np.zeros_like(d)
 L.model_twopass(d.ctypes.data_as(vp), yd.ctypes.data_as(vp), i64(d.size))
