@@ -148,6 +148,15 @@ TP_API int softmax3p_onchip_f16io(const uint16_t *x, uint16_t *y, int64_t rows, 
 TP_API int softmax_tp_extexp_f32(const float *x, float *m, float *e, int64_t count, void *stream);
 
 /*
+ * The same pairs from the other evaluator Section 4 allows for the reduced argument: base-2
+ * reduction with a two-term log2 e and the hardware's 2^f instruction instead of the
+ * polynomial.  Same e[i] as softmax_tp_extexp_f32, m[i] within 1 ULP or so of it.  Not used
+ * by the softmax entry points (it is not faster on this part); here for comparison.
+ */
+TP_API int softmax_tp_extexp_hw_f32(const float *x, float *m, float *e, int64_t count,
+                                    void *stream);
+
+/*
  * Pass 1 of Algorithm 3 including every merge level: pairs[2 r] = m_sum and
  * pairs[2 r + 1] = n_sum of row r.  pairs is a device pointer to 2 * rows floats.
  */

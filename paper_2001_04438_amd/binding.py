@@ -35,6 +35,7 @@ ENTRY_POINTS = {
     "softmax3p_onchip_bf16io": [_vp, _vp, _i64, _i64, _vp],
     "softmax3p_onchip_f16io": [_vp, _vp, _i64, _i64, _vp],
     "softmax_tp_extexp_f32": [_vp, _vp, _vp, _i64, _vp],
+    "softmax_tp_extexp_hw_f32": [_vp, _vp, _vp, _i64, _vp],
     "softmax2p_f32_pass1": [_vp, _vp, _i64, _i64, _vp],
     "softmax2p_f32_pass2": [_vp, _vp, _vp, _i64, _i64, _vp],
     "softmax_tp_stream_read_f32": [_vp, _vp, _i64, _vp],
@@ -213,6 +214,11 @@ def softmax3p_onchip_f16io(x, y, rows, n, stream=None):
 def softmax_tp_extexp_f32(x, m, e, count, stream=None):
     _check("softmax_tp_extexp_f32",
            lib().softmax_tp_extexp_f32(_addr(x), _addr(m), _addr(e), count, _stream(stream)))
+
+
+def softmax_tp_extexp_hw_f32(x, m, e, count, stream=None):
+    _check("softmax_tp_extexp_hw_f32",
+           lib().softmax_tp_extexp_hw_f32(_addr(x), _addr(m), _addr(e), count, _stream(stream)))
 
 
 def softmax2p_f32_pass1(x, pairs, rows, n, stream=None):

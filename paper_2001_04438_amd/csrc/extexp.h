@@ -60,3 +60,22 @@ TP_FN void tp_extexp_scaled(float x, const float *cs, float *ms, float *n)
     *ms = p;
     *n = nn;
 }
+
+#if defined(__HIPCC__)
+// The alternative the paper leaves open for step 2 of the exponential (Section 4: the
+// function on the reduced argument may also come from a table or another approximation):
+// reduce in base 2, f = x log2 e - n with log2 e split in two fp32 terms (the first product
+// is exact inside the FMA), and take 2^f from the hardware's v_exp_f32.  Same n as
+// tp_extexp, so the two are interchangeable per element.  Built into the softmax kernels it
+// gained 2-3 % on rows of 16-bit elements, which are bound by vector instructions, nothing
+// on fp32 and cost the on-chip fp32 kernel its register budget, so the kernels keep the
+// polynomial; this evaluator stays exported on its own for the accuracy test.
+__device__ __forceinline__ void tp_extexp_hw(float x, float *m, float *n)
+{
+    float nn = __builtin_rintf(x * TP_LOG2E);
+    float f = __builtin_fmaf(x, TP_LOG2E, -nn);
+    f = __builtin_fmaf(x, TP_LOG2E_LO, f);
+    *m = __builtin_amdgcn_exp2f(f);
+    *n = nn;
+}
+#endif

@@ -731,7 +731,7 @@ int softmax3p_onchip_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_
     return run_onchip<BF16x8>(kOnchipThreePass, x, y, rows, n, stream);
 }
 
-int softmax_tp_extexp_f32(const float *x, float *m, float *e, int64_t count, void *stream)
+static int run_extexp(bool hw, const float *x, float *m, float *e, int64_t count, void *stream)
 {
     if (count < 0)
         return TP_ERR_NEGATIVE;
@@ -744,9 +744,23 @@ int softmax_tp_extexp_f32(const float *x, float *m, float *e, int64_t count, voi
     int64_t blocks = (count + 255) / 256;
     if (blocks > 65536)
         blocks = 65536;
-    hipLaunchKernelGGL(extexp_kernel, dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream, x,
-                       m, e, count);
+    if (hw)
+        hipLaunchKernelGGL(extexp_kernel<true>, dim3((uint32_t)blocks), dim3(256), 0,
+                           (hipStream_t)stream, x, m, e, count);
+    else
+        hipLaunchKernelGGL(extexp_kernel<false>, dim3((uint32_t)blocks), dim3(256), 0,
+                           (hipStream_t)stream, x, m, e, count);
     return launch_status();
+}
+
+int softmax_tp_extexp_f32(const float *x, float *m, float *e, int64_t count, void *stream)
+{
+    return run_extexp(false, x, m, e, count, stream);
+}
+
+int softmax_tp_extexp_hw_f32(const float *x, float *m, float *e, int64_t count, void *stream)
+{
+    return run_extexp(true, x, m, e, count, stream);
 }
 
 // The pass-level entry points always use the chunk kernels, also for shapes the full

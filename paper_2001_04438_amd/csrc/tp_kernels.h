@@ -558,13 +558,18 @@ __global__ __launch_bounds__(kMergeBlock) void merge_sum_kernel(const float *par
 
 // ---- ExtExp alone ------------------------------------------------------------
 
+template <bool HW>
 __global__ __launch_bounds__(256) void extexp_kernel(const float *x, float *m, float *e,
                                                      int64_t count)
 {
     int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t step = (int64_t)gridDim.x * 256;
-    for (; i < count; i += step)
-        tp_extexp(x[i], &m[i], &e[i]);
+    for (; i < count; i += step) {
+        if constexpr (HW)
+            tp_extexp_hw(x[i], &m[i], &e[i]);
+        else
+            tp_extexp(x[i], &m[i], &e[i]);
+    }
 }
 
 }  // namespace tp

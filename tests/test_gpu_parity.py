@@ -413,7 +413,8 @@ def test_shift_invariance_on_gpu(gpu):
 # pieces of the path: ExtExp, pass 1 pairs, pass 2
 # ---------------------------------------------------------------------------
 
-def test_extexp_pairs(gpu, oracle_mod):
+@pytest.mark.parametrize("name", ["softmax_tp_extexp_f32", "softmax_tp_extexp_hw_f32"])
+def test_extexp_pairs(gpu, oracle_mod, name):
     import torch
     rng = np.random.default_rng(82)
     xs = np.concatenate([
@@ -423,9 +424,14 @@ def test_extexp_pairs(gpu, oracle_mod):
     xd = torch.from_numpy(xs).cuda()
     md = torch.empty_like(xd)
     ed = torch.empty_like(xd)
-    gpu.softmax_tp_extexp_f32(xd, md, ed, xs.size)
+    getattr(gpu, name)(xd, md, ed, xs.size)
     torch.cuda.synchronize()
     m, e = md.cpu().numpy(), ed.cpu().numpy()
+    if name.endswith("hw_f32"):            # both evaluators split x at the same n
+        m0, e0 = torch.empty_like(xd), torch.empty_like(xd)
+        gpu.softmax_tp_extexp_f32(xd, m0, e0, xs.size)
+        assert torch.equal(e0, ed)
+        assert float(((m0 - md).abs() / m0).max()) < 4e-7
     assert np.all(e == np.rint(e))                                   # n is an integer
     assert np.all(np.abs(e - xs.astype(np.float64) * 1.4426950408889634) <= 0.5 + 1e-2)
     inner = np.abs(xs) <= 1e4
