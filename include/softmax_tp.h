@@ -221,6 +221,8 @@ TP_API int softmax_tp_plan(int64_t rows, int64_t n, int32_t elem_bytes, int32_t 
  *   "direction"       1: every pass walks memory forwards; 2 (default): successive
  *                     passes alternate direction
  *   "nt_first"        1: first read of x cacheable; 2: non-temporal; default: by size
+ *   "fold_max"        most partial results per row that a consuming pass folds by itself;
+ *                     more than that go through a merge kernel first (at most 4096)
  * block is 256, 512 or 1024; unroll 2, 4 or 8 (bf16: 2 or 4).  value 0 restores the
  * default.  Not thread safe against running calls.
  */

@@ -25,13 +25,17 @@ struct Tuning {
     int64_t block_mapsum = 0, unroll_mapsum = 0, tiles_mapsum = 0;
     int64_t direction = 0;
     int64_t nt_first = 0;
+    int64_t fold_max = 0;
 };
 static Tuning g_tune;
 
 constexpr int64_t kRowsPathMaxBytes = 256 * 1024;  // longest row one workgroup takes
 constexpr int64_t kRowsPathMinRows = 32;           // fewer rows than this cannot fill the chip
 constexpr int64_t kSmallRowBytes = 128 * 1024;     // ... unless the rows are this short (one launch wins)
-constexpr int64_t kTargetReduce = 1024;            // workgroups of a read-only pass (4 per CU)
+// Partials per row a consuming pass folds itself.  Every wave of the launch reads them, so
+// the limit is low: 128 still beat a merge launch (1.3 %), 512 lost 10 % on the 1 GiB vector.
+constexpr int kFoldMax = 128;
+constexpr int64_t kTargetReduce = 512;             // workgroups of a read-only pass (2 per CU)
 constexpr int64_t kNtFirstBytes = (int64_t)512 << 20;  // inputs beyond this outlive every cache
 // A launch may hold at most 2^32 - 1 threads in all (and 2^31 - 1 workgroups); grids are
 // rounded up to a multiple of kXcds, hence the margin.
@@ -144,9 +148,11 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
     }
 
     p->path = 2;
-    // read-only passes: few, long chunks (a read stream likes to stay in one workgroup)
+    // read-only passes: few, long chunks.  Two workgroups of four waves per CU, each lane with
+    // four 16-byte loads in flight (8 MiB over the chip), stream fastest; more waves or deeper
+    // queues only add contention at the memory channels.
     {
-        const int block = g_tune.block_reduce ? (int)g_tune.block_reduce : 512;
+        const int block = g_tune.block_reduce ? (int)g_tune.block_reduce : 256;
         const int unroll = g_tune.unroll_reduce ? (int)g_tune.unroll_reduce : 4;
         const int64_t target = g_tune.target_reduce ? g_tune.target_reduce : kTargetReduce;
         int64_t per_row = (target + rows - 1) / rows;
@@ -154,12 +160,14 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
         int rc = chunk_shape(rows, nvec, block, unroll, (nvec + per_row - 1) / per_row, &p->reduce);
         if (rc != TP_OK) return rc;
     }
-    // read-write passes: many short-lived workgroups (two rounds each), so that hardly any
-    // load has to queue behind the stores of an earlier round of the same wave
+    // read-write passes: many short-lived workgroups of one round each, so that no load has to
+    // queue behind the stores of an earlier round of the same wave; smaller workgroups when the
+    // whole array is short, where the ramp and the tail of the launch weigh more
     {
-        const int block = g_tune.block_map ? (int)g_tune.block_map : 512;
+        const int block = g_tune.block_map ? (int)g_tune.block_map
+                                           : (rows * row_bytes >= kNtFirstBytes ? 512 : 256);
         const int unroll = g_tune.unroll_map ? (int)g_tune.unroll_map : 2;
-        const int64_t tiles = g_tune.tiles_map ? g_tune.tiles_map : 2;
+        const int64_t tiles = g_tune.tiles_map ? g_tune.tiles_map : 1;
         int rc = chunk_shape(rows, nvec, block, unroll, tiles * block * unroll, &p->map);
         if (rc != TP_OK) return rc;
     }
@@ -177,7 +185,7 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
     p->nt_first_load = g_tune.nt_first ? (g_tune.nt_first == 2)
                                        : (rows * row_bytes >= kNtFirstBytes);
     // up to kFoldMax partials per row are folded by the consuming pass itself
-    p->merge_kernel = p->reduce.chunks > kFoldMax ? 1 : 0;
+    p->merge_kernel = p->reduce.chunks > (g_tune.fold_max ? g_tune.fold_max : kFoldMax) ? 1 : 0;
     p->launches = 2 + p->merge_kernel;
     const int64_t most = p->reduce.chunks > p->mapsum.chunks ? p->reduce.chunks : p->mapsum.chunks;
     p->workspace_bytes = (2 * rows * most + 2 * rows) * (int64_t)sizeof(float);
@@ -246,6 +254,8 @@ static dim3 chunk_grid(int64_t rows, const softmax_tp_shape_t &s)
 }
 
 // pass k of a call (0-based) runs backwards when k is odd, unless tuned otherwise
+static int fold_max() { return g_tune.fold_max ? (int)g_tune.fold_max : kFoldMax; }
+
 static bool pass_reversed(int k) { return g_tune.direction == 1 ? false : (k & 1) != 0; }
 
 template <int N>
@@ -402,7 +412,7 @@ static int run_chunks_3p(Algo algo, const softmax_tp_plan_t &plan, const typenam
         });
         if (rc != TP_OK)
             return rc;
-        if (nmax > kFoldMax) {
+        if (nmax > fold_max()) {
             hipLaunchKernelGGL(merge_max_kernel, merge_grid, merge_block, 0, st, pmax, nmax, rowmax);
             if ((rc = launch_status()) != TP_OK)
                 return rc;
@@ -435,7 +445,7 @@ static int run_chunks_3p(Algo algo, const softmax_tp_plan_t &plan, const typenam
     }
     if (rc != TP_OK)
         return rc;
-    if (nsum > kFoldMax) {
+    if (nsum > fold_max()) {
         hipLaunchKernelGGL(merge_sum_kernel, merge_grid, merge_block, 0, st, psum, nsum, rowsum);
         if ((rc = launch_status()) != TP_OK)
             return rc;
@@ -903,6 +913,7 @@ int softmax_tp_tune(const char *key, int64_t value)
         {"tiles_mapsum", &g_tune.tiles_mapsum, kAny},
         {"direction", &g_tune.direction, kThree},
         {"nt_first", &g_tune.nt_first, kThree},
+        {"fold_max", &g_tune.fold_max, kAny},
     };
     for (auto &k : keys) {
         if (std::strcmp(key, k.name) != 0)
@@ -911,6 +922,7 @@ int softmax_tp_tune(const char *key, int64_t value)
             if (k.kind == kBlock && !valid_block(value)) return TP_ERR_TUNING;
             if (k.kind == kUnroll && !valid_unroll(value, 4)) return TP_ERR_TUNING;
             if (k.kind == kThree && value > 2) return TP_ERR_TUNING;
+            if (k.slot == &g_tune.fold_max && value > 4096) return TP_ERR_TUNING;
         }
         *k.slot = value;
         return TP_OK;

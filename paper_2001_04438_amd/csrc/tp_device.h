@@ -103,20 +103,20 @@ __device__ __forceinline__ void wave_pair(float &m, float &n)
     n = nw;
 }
 
-// A row's few (<= 64) partial results folded by every wave on its own: lane i takes
-// partial i, then the wave reduction.  No LDS, no barrier, and every wave of every
-// workgroup gets the bit-identical value.
-constexpr int kFoldMax = kWave;
-
+// A row's partial results folded by every wave on its own: lane i takes partials i,
+// i + 64, ... in that order, then the wave reduction.  No LDS, no barrier, and every wave of
+// every workgroup gets the bit-identical value.  The partials are read by all the waves of a
+// launch, so the host sends more than a hundred or so through a merge kernel first.
 __device__ __forceinline__ void wave_fold_pairs(const float2 *p, int cnt, float &m, float &n)
 {
     const int lane = threadIdx.x & (kWave - 1);
     m = 0.f;
     n = kNIdent;
-    if (lane < cnt) {
-        const float2 q = p[lane];
-        m = q.x;
-        n = q.y;
+    for (int k = lane; k < cnt; k += kWave) {
+        const float2 q = p[k];
+        const float nn = fmaxf(n, q.y);
+        m = scale_pow2(m, n - nn) + scale_pow2(q.x, q.y - nn);
+        n = nn;
     }
     wave_pair(m, n);
 }
@@ -124,13 +124,19 @@ __device__ __forceinline__ void wave_fold_pairs(const float2 *p, int cnt, float 
 __device__ __forceinline__ float wave_fold_max(const float *p, int cnt)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    return wave_max(lane < cnt ? p[lane] : -__builtin_inff());
+    float v = -__builtin_inff();
+    for (int k = lane; k < cnt; k += kWave)
+        v = fmaxf(v, p[k]);
+    return wave_max(v);
 }
 
 __device__ __forceinline__ float wave_fold_sum(const float *p, int cnt)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    return wave_sum(lane < cnt ? p[lane] : 0.f);
+    float v = 0.f;
+    for (int k = lane; k < cnt; k += kWave)
+        v += p[k];
+    return wave_sum(v);
 }
 
 // ---------------------------------------------------------------------------

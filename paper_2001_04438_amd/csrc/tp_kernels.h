@@ -4,8 +4,8 @@
 //             algorithm in one launch; the re-read of the row comes from L2.
 // chunk path  chunk_*: a row is cut into chunks, one workgroup each.  A reducing
 //             pass leaves one partial result per chunk.  The next pass folds up to
-//             64 partials per row itself (one per lane, a wave reduction); beyond
-//             that merge_* folds them into one value per row first.
+//             128 partials per row itself (lane i takes partials i, i + 64, then a wave
+//             reduction); beyond that merge_* folds them into one value per row first.
 #pragma once
 #include "tp_device.h"
 
@@ -390,7 +390,7 @@ __global__ __launch_bounds__(BLOCK) void chunk_2p_pass1(const typename IO::elem 
         partial[wg] = make_float2(acc.m, acc.n);
 }
 
-// Two-Pass pass 2.  pairs holds `npairs` (<= 64) pairs per row: the chunk partials of
+// Two-Pass pass 2.  pairs holds `npairs` (a few) pairs per row: the chunk partials of
 // pass 1, or the single merged pair.
 template <class IO, int BLOCK, int U>
 __global__ __launch_bounds__(BLOCK) void chunk_2p_pass2(const typename IO::elem *x,
@@ -462,7 +462,7 @@ __global__ __launch_bounds__(BLOCK) void chunk_expstore(const typename IO::elem 
         psum[wg] = v;
 }
 
-// y = x / sigma (reload pass 3, x == y; `nsum` <= 64 partial sums per row);
+// y = x / sigma (reload pass 3, x == y; `nsum` partial sums per row, a few);
 // with sums == nullptr: y = lambda * x.
 template <class IO, int BLOCK, int U>
 __global__ __launch_bounds__(BLOCK) void chunk_scale(const typename IO::elem *x,

@@ -129,7 +129,7 @@ def test_cfg4_single_long_vector(gpu, oracle_mod, name, tol):
     n = (1 << 23) + 3  # thousands of chunks, ragged tail
     x = workloads.cfg4(n=n)
     plan = gpu.softmax_tp_plan(1, n)
-    assert plan.path == 2 and plan.reduce.chunks >= 512 and plan.map.chunks >= 1024
+    assert plan.path == 2 and plan.merge_kernel == 1 and plan.map.chunks >= 1024
     c = _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
     assert c.n_normal < x.size // 100  # almost everything underflows next to the outliers
 
@@ -511,6 +511,29 @@ def test_launch_shapes(gpu, oracle_mod):
                     _check(oracle_mod, xb, _run(gpu.softmax2p_bf16io, xb), TOL_BF16, bf16=True)
     finally:
         gpu.softmax_tp_tune_reset()
+
+
+@pytest.mark.parametrize("name,tol", ALGOS_F32)
+def test_partials_folded_by_the_consuming_pass(gpu, oracle_mod, name, tol):
+    """65..128 partials per row: lanes fold two each; the fold_max key moves the hand-over
+    to the merge kernel either way."""
+    fn = getattr(gpu, name)
+    for rows, n in ((4, 600_001), (4, 900_001)):
+        plan = gpu.softmax_tp_plan(rows, n)
+        assert plan.path == 2 and 64 < plan.reduce.chunks <= 128 and plan.merge_kernel == 0
+        x = workloads.cfg3(rows=rows, n=n)
+        want = _run(fn, x)
+        _check(oracle_mod, x, want, tol)
+        try:
+            gpu.softmax_tp_tune("fold_max", 64)
+            assert gpu.softmax_tp_plan(rows, n).merge_kernel == 1
+            _check(oracle_mod, x, _run(fn, x), tol)
+            gpu.softmax_tp_tune("fold_max", 512)
+            x1 = workloads.cfg3(rows=1, n=3_000_017)
+            assert gpu.softmax_tp_plan(1, 3_000_017).merge_kernel == 0
+            _check(oracle_mod, x1, _run(fn, x1), tol)
+        finally:
+            gpu.softmax_tp_tune("fold_max", 0)
 
 
 def test_bitwise_reproducible(gpu):

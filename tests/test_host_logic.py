@@ -73,11 +73,15 @@ def test_planner_on_the_benchmark_configurations(B):
     plans = [B.softmax_tp_plan(r, n, s) for r, n, s in CONFIGS]
     assert [p.path for p in plans] == [1, 1, 2, 2, 1]
     assert [p.launches for p in plans] == [1, 1, 2, 3, 1]
-    assert plans[2].merge_kernel == 0 and plans[2].reduce.chunks <= 64   # folded by pass 2 itself
-    assert plans[3].merge_kernel == 1 and plans[3].reduce.chunks > 64
+    assert plans[2].merge_kernel == 0 and plans[2].reduce.chunks <= 128  # folded by pass 2 itself
+    assert plans[3].merge_kernel == 1 and plans[3].reduce.chunks > 128
     assert plans[1].rows.block == 1024                      # config 2: one workgroup per row
     assert plans[4].vector_elems == 8 and plans[4].rows.unroll <= 4
     assert plans[3].nt_first_load == 1 and plans[2].nt_first_load == 0
+    # read-only passes: two workgroups of 256 threads per CU; read-write passes: one round each
+    assert (plans[3].reduce.block, plans[3].reduce.unroll, plans[3].reduce.chunks) == (256, 4, 512)
+    assert (plans[3].map.block, plans[3].map.unroll, plans[3].map.chunk_vecs) == (512, 2, 1024)
+    assert (plans[2].map.block, plans[2].map.chunk_vecs, plans[2].reduce.chunks) == (256, 512, 8)
     for (rows, n, s), p in zip(CONFIGS, plans):
         if p.path != 2:
             continue
@@ -139,7 +143,8 @@ def test_tuning_keys(B):
         with pytest.raises(B.SoftmaxTpError):
             B.softmax_tp_tune(key, bad)
     B.softmax_tp_tune_reset()
-    assert B.softmax_tp_plan(2, 10_000_000).map.block == 512
+    assert B.softmax_tp_plan(2, 10_000_000).map.block == 256     # short arrays: smaller workgroups
+    assert B.softmax_tp_plan(1, 1 << 28).map.block == 512
 
 
 def test_constants_header_is_what_the_generator_writes():
