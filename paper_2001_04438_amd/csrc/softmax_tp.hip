@@ -35,6 +35,7 @@ constexpr int64_t kSmallRowBytes = 128 * 1024;     // ... unless the rows are th
 // Partials per row a consuming pass folds itself.  Every wave of the launch reads them, so
 // the limit is low: 128 still beat a merge launch (1.3 %), 512 lost 10 % on the 1 GiB vector.
 constexpr int kFoldMax = 128;
+constexpr int64_t kLatencyBoundBytes = (int64_t)4 << 20;  // below this a launch costs more than its traffic
 constexpr int64_t kTargetReduce = 512;             // workgroups of a read-only pass (2 per CU)
 constexpr int64_t kNtFirstBytes = (int64_t)512 << 20;  // inputs beyond this outlive every cache
 // A launch may hold at most 2^32 - 1 threads in all (and 2^31 - 1 workgroups); grids are
@@ -148,6 +149,7 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
     }
 
     p->path = 2;
+    const int64_t fold_limit = g_tune.fold_max ? g_tune.fold_max : kFoldMax;
     // read-only passes: few, long chunks.  Two workgroups of four waves per CU, each lane with
     // four 16-byte loads in flight (8 MiB over the chip), stream fastest; more waves or deeper
     // queues only add contention at the memory channels.
@@ -157,6 +159,10 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
         const int64_t target = g_tune.target_reduce ? g_tune.target_reduce : kTargetReduce;
         int64_t per_row = (target + rows - 1) / rows;
         if (per_row < 1) per_row = 1;
+        // short inputs are bound by launch latency: stay within what the next pass folds by
+        // itself, which saves the merge launch
+        if (rows * row_bytes <= kLatencyBoundBytes && per_row > fold_limit && !g_tune.target_reduce)
+            per_row = fold_limit;
         int rc = chunk_shape(rows, nvec, block, unroll, (nvec + per_row - 1) / per_row, &p->reduce);
         if (rc != TP_OK) return rc;
     }
@@ -185,7 +191,7 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
     p->nt_first_load = g_tune.nt_first ? (g_tune.nt_first == 2)
                                        : (rows * row_bytes >= kNtFirstBytes);
     // up to kFoldMax partials per row are folded by the consuming pass itself
-    p->merge_kernel = p->reduce.chunks > (g_tune.fold_max ? g_tune.fold_max : kFoldMax) ? 1 : 0;
+    p->merge_kernel = p->reduce.chunks > fold_limit ? 1 : 0;
     p->launches = 2 + p->merge_kernel;
     const int64_t most = p->reduce.chunks > p->mapsum.chunks ? p->reduce.chunks : p->mapsum.chunks;
     p->workspace_bytes = (2 * rows * most + 2 * rows) * (int64_t)sizeof(float);

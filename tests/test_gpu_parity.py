@@ -518,7 +518,7 @@ def test_partials_folded_by_the_consuming_pass(gpu, oracle_mod, name, tol):
     """65..128 partials per row: lanes fold two each; the fold_max key moves the hand-over
     to the merge kernel either way."""
     fn = getattr(gpu, name)
-    for rows, n in ((4, 600_001), (4, 900_001)):
+    for rows, n in ((4, 1_200_001), (4, 1_500_001)):
         plan = gpu.softmax_tp_plan(rows, n)
         assert plan.path == 2 and 64 < plan.reduce.chunks <= 128 and plan.merge_kernel == 0
         x = workloads.cfg3(rows=rows, n=n)
