@@ -218,7 +218,7 @@ TP_API int softmax_tp_plan(int64_t rows, int64_t n, int32_t elem_bytes, int32_t 
  *   "block_map", "unroll_map", "tiles_map"  read-write passes: shape and tiles
  *                     (block * unroll vectors) per workgroup
  *   "block_mapsum", "unroll_mapsum", "tiles_mapsum"  the same for the exp-store pass
- *   "direction"       1: every pass walks memory forwards; 2 (default): successive
+ *   "direction"       1 (default): every pass walks memory forwards; 2: successive
  *                     passes alternate direction
  *   "nt_first"        1: first read of x cacheable; 2: non-temporal; default: by size
  *   "fold_max"        most partial results per row that a consuming pass folds by itself;

@@ -259,10 +259,13 @@ static dim3 chunk_grid(int64_t rows, const softmax_tp_shape_t &s)
     return dim3((uint32_t)((total + kXcds - 1) / kXcds * kXcds));
 }
 
-// pass k of a call (0-based) runs backwards when k is odd, unless tuned otherwise
 static int fold_max() { return g_tune.fold_max ? (int)g_tune.fold_max : kFoldMax; }
 
-static bool pass_reversed(int k) { return g_tune.direction == 1 ? false : (k & 1) != 0; }
+// Every pass walks memory forwards.  With the tuning key "direction" = 2, pass k of a call
+// (0-based) runs backwards when k is odd, so that it starts on what the previous pass touched
+// last; on this part that measured the same or slightly worse, the caches being small next to
+// the arrays that take this path.
+static bool pass_reversed(int k) { return g_tune.direction == 2 && (k & 1) != 0; }
 
 template <int N>
 using ic = std::integral_constant<int, N>;
