@@ -231,6 +231,8 @@ TP_API int softmax_tp_tune(const char *key, int64_t value);
 /*
  * Allocates (or grows) the workspace a later softmax call with this shape on this stream
  * would need, so that the call itself does not allocate.  Shapes on the rows path need none.
+ * After it, a softmax call on that stream consists of kernel launches only (no allocation,
+ * no memset, no host synchronisation) and can be captured into a HIP graph and replayed.
  */
 TP_API int softmax_tp_reserve(int64_t rows, int64_t n, int32_t elem_bytes, void *stream);
 

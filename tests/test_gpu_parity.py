@@ -595,6 +595,41 @@ def test_reserve_and_release(gpu, oracle_mod):
         gpu.softmax_tp_reserve(-1, 5)
 
 
+def test_capture_into_a_graph_and_replay(gpu, oracle_mod):
+    """A serving loop captures the call once and replays it: no allocation, no host
+    synchronisation and no memset may hide in the call once its workspace is reserved."""
+    import torch
+    side = torch.cuda.Stream()
+    cases = [("softmax2p_f32", 3, 700_001, TOL_2P),            # chunk path, pass 2 folds the partials
+             ("softmax2p_f32", 1, 3_000_017, TOL_2P),          # chunk path with the merge launch
+             ("softmax3p_reload_f32", 2, 1_500_000, TOL_3P),   # five launches
+             ("softmax2p_f32", 300, 5000, TOL_2P),             # rows path
+             ("softmax2p_onchip_f32", 300, 5000, TOL_2P)]
+    for name, rows, n, tol in cases:
+        fn = getattr(gpu, name)
+        x = torch.empty(rows * n, dtype=torch.float32, device="cuda")
+        y = torch.full_like(x, -7.0)
+        want = torch.empty_like(x)
+        gpu.softmax_tp_reserve(rows, n, 4, stream=side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            fn(x, y, rows, n)                                  # launched on the capturing stream
+        for trial in range(3):
+            host = workloads.cfg3(rows=rows, n=n) + np.float32(trial)
+            x.copy_(torch.from_numpy(host.reshape(-1)))
+            y.fill_(-7.0)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            fn(x, want, rows, n)                               # eager, default stream
+            torch.cuda.synchronize()
+            assert torch.equal(y, want), (name, rows, n, trial)
+            if trial == 2:
+                _check(oracle_mod, host, y.cpu().numpy().reshape(rows, n), tol)
+        del graph
+
+
 def test_calibration_streams(gpu):
     import torch
     n = (1 << 22) + 5
