@@ -60,6 +60,10 @@ def time_calls(torch, fn, steps, warmup, sets):
 
 
 WAKEUP_S = 0.25
+# 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz, one fp32 operation per lane and clock
+# (packed fp32 arithmetic is not used)
+VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+VALU_OPS_PER_ELEM_16BIT = (244 + 228) / 16
 
 
 def wake_up(torch, fn, sets):
@@ -167,6 +171,14 @@ def run_workload(torch, B, W, name, steps, warmup, full):
         k = per_launch_ms(torch, lambda i: fn(xs[i], ys[i], rows, n), steps, sets)
         out["kernel_ms"] = {"avg": k[0], "median": k[1], "min": k[2]}
         dom_name, dom_ms, dom_bytes = "rows_2p", k[0], 3 * elems * s
+    if s == 2 and plan.path == 1:
+        # rows of 16-bit elements are bound by vector arithmetic, not by memory: the compiled
+        # loops of rows_2p issue 244 (pass 1) + 228 (pass 2) vector instructions per 16 elements
+        ops = VALU_OPS_PER_ELEM_16BIT * elems
+        out["alu_roofline"] = {"bound": "alu", "kernel": dom_name,
+                               "lane_ops_per_element": VALU_OPS_PER_ELEM_16BIT,
+                               "achieved": ops / dom_ms / 1e9, "peak": VALU_PEAK_TOPS,
+                               "unit": "T lane-operations/s", "frac": ops / dom_ms / 1e9 / VALU_PEAK_TOPS}
     out["dominant"] = {"kernel": dom_name, "avg_ms": dom_ms, "algorithmic_bytes": dom_bytes,
                        "GBps": dom_bytes / dom_ms / 1e6,
                        "traffic_bytes": load_traffic(name, dom_name)}
@@ -329,6 +341,8 @@ def main():
                                                       "frac_of_hbm_peak")}
                              for k, v in o["variants"].items()},
                 "dominant": o["dominant"]}
+            if "alu_roofline" in o:
+                others[name]["alu_roofline"] = o["alu_roofline"]
         result["other_workloads"] = others
     B.softmax_tp_release()
     print(json.dumps(result))
