@@ -95,6 +95,22 @@ def test_planner_on_the_benchmark_configurations(B):
         assert p.workspace_bytes <= 1 << 20
 
 
+def test_planner_avoids_the_merge_launch_on_short_inputs(B):
+    # up to 4 MiB a launch costs more than its traffic: at most 128 chunks, folded by the next pass
+    for n in (1 << 16, 1 << 18, 1 << 20):
+        p = B.softmax_tp_plan(1, n)
+        assert p.path == 2 and p.reduce.chunks <= 128 and p.merge_kernel == 0 and p.launches == 2
+    p = B.softmax_tp_plan(1, (1 << 20) + 1)
+    assert p.reduce.chunks > 128 and p.merge_kernel == 1 and p.launches == 3
+    p = B.softmax_tp_plan(4, 1 << 24)
+    assert p.reduce.chunks == 128 and p.merge_kernel == 0      # 512 workgroups over four rows
+    B.softmax_tp_tune("fold_max", 64)
+    assert B.softmax_tp_plan(4, 1 << 24).merge_kernel == 1
+    B.softmax_tp_tune("fold_max", 0)
+    with pytest.raises(B.SoftmaxTpError):
+        B.softmax_tp_tune("fold_max", 5000)
+
+
 def test_planner_covers_odd_shapes(B):
     rng = np.random.default_rng(3)
     for _ in range(300):
