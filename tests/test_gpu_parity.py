@@ -199,6 +199,16 @@ def test_short_rows_one_wave_each(gpu, oracle_mod, name, tol):
     _check(oracle_mod, x, _run(getattr(gpu, name), x, inplace=True), tol)
 
 
+@pytest.mark.parametrize("name,tol", ALGOS_F32)
+def test_very_many_rows(gpu, oracle_mod, name, tol):
+    """Grids of hundreds of thousands of workgroups: one wave per row and one workgroup per row."""
+    rng = np.random.default_rng(85)
+    for rows, n in (((1 << 20) + 3, 7), (300_001, 64), (70_001, 1500)):
+        x = rng.normal(0, 3, size=(rows, n)).astype(np.float32)
+        c = _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
+        assert c.n_total == rows * n
+
+
 def test_short_rows_one_wave_each_bf16(gpu, oracle_mod):
     rng = np.random.default_rng(84)
     for name in ("softmax2p_bf16io", "softmax3p_recompute_bf16io", "softmax3p_reload_bf16io"):
