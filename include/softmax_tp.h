@@ -29,6 +29,10 @@
  *            workspace owned by the library (a few KB to a few hundred KB per
  *            stream), allocated on first use and kept; softmax_tp_release()
  *            frees it.  The library allocates nothing else.
+ *   threads  several host threads may call at once provided no two of them use the
+ *            same stream at the same time (two calls interleaved on one stream would
+ *            share that stream's workspace).  softmax_tp_tune and
+ *            softmax_tp_release must not run concurrently with any other call.
  */
 #ifndef SOFTMAX_TP_H
 #define SOFTMAX_TP_H
