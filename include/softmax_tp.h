@@ -227,7 +227,8 @@ TP_API int softmax_tp_plan(int64_t rows, int64_t n, int32_t elem_bytes, int32_t 
  *   "nt_first"        1: first read of x cacheable; 2: non-temporal; default: by size
  *   "fold_max"        most partial results per row that a consuming pass folds by itself;
  *                     more than that go through a merge kernel first (at most 4096)
- * block is 256, 512 or 1024; unroll 2, 4 or 8 (bf16: 2 or 4).  value 0 restores the
+ * block is 256, 512 or 1024; unroll 2, 4 or 8 (16-bit formats: 2 or 4); in addition the
+ * pair block 128, unroll 1.  value 0 restores the
  * default.  Not thread safe against running calls.
  */
 TP_API int softmax_tp_tune(const char *key, int64_t value);

@@ -44,10 +44,10 @@ constexpr int64_t kThreadsMax = 0xFFFFFFFFll - 16 * 1024;
 constexpr int64_t kGridMax = 0x7FFFFFF0;
 constexpr int64_t kChunkVecsMax = (int64_t)1 << 26;  // a chunk is indexed with 32-bit offsets
 
-static bool valid_block(int64_t b) { return b == 256 || b == 512 || b == 1024; }
+static bool valid_block(int64_t b) { return b == 128 || b == 256 || b == 512 || b == 1024; }
 static bool valid_unroll(int64_t u, int elem_bytes)
 {
-    return u == 2 || u == 4 || (u == 8 && elem_bytes == 4);
+    return u == 1 || u == 2 || u == 4 || (u == 8 && elem_bytes == 4);
 }
 
 // Rows path: the largest tile (block * unroll vectors per round) that wastes at
@@ -166,14 +166,16 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
         int rc = chunk_shape(rows, nvec, block, unroll, (nvec + per_row - 1) / per_row, &p->reduce);
         if (rc != TP_OK) return rc;
     }
-    // read-write passes: many short-lived workgroups of one round each, so that no load has to
-    // queue behind the stores of an earlier round of the same wave; smaller workgroups when the
-    // whole array is short, where the ramp and the tail of the launch weigh more
+    // read-write passes: many short-lived workgroups, so that hardly any load has to queue
+    // behind the stores of an earlier round of the same wave.  Arrays beyond the caches stream
+    // fastest with one 16-byte access per lane at a time (two rounds of a 128-thread
+    // workgroup); shorter ones, where the ramp and the tail of the launch weigh more, with one
+    // round of 256 threads x 2.
     {
-        const int block = g_tune.block_map ? (int)g_tune.block_map
-                                           : (rows * row_bytes >= kNtFirstBytes ? 512 : 256);
-        const int unroll = g_tune.unroll_map ? (int)g_tune.unroll_map : 2;
-        const int64_t tiles = g_tune.tiles_map ? g_tune.tiles_map : 1;
+        const bool big = rows * row_bytes >= kNtFirstBytes;
+        const int block = g_tune.block_map ? (int)g_tune.block_map : (big ? 128 : 256);
+        const int unroll = g_tune.unroll_map ? (int)g_tune.unroll_map : (big ? 1 : 2);
+        const int64_t tiles = g_tune.tiles_map ? g_tune.tiles_map : (big ? 2 : 1);
         int rc = chunk_shape(rows, nvec, block, unroll, tiles * block * unroll, &p->map);
         if (rc != TP_OK) return rc;
     }
@@ -285,6 +287,7 @@ static int with_shape(const softmax_tp_shape_t &s, F &&f)
             return launch_status();                                          \
         }
     switch (s.block * 16 + s.unroll) {
+        TP_CASE(128, 1)
         TP_CASE(256, 2) TP_CASE(256, 4) TP_CASE(256, 8)
         TP_CASE(512, 2) TP_CASE(512, 4) TP_CASE(512, 8)
         TP_CASE(1024, 2) TP_CASE(1024, 4) TP_CASE(1024, 8)

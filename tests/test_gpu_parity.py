@@ -519,6 +519,21 @@ def test_launch_shapes(gpu, oracle_mod):
                     for name, tol in ALGOS_F32:
                         _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
                     _check(oracle_mod, xb, _run(gpu.softmax2p_bf16io, xb), TOL_BF16, bf16=True)
+        # the read-write shape used for arrays beyond the caches: 128 threads, one access each
+        gpu.softmax_tp_tune_reset()
+        gpu.softmax_tp_tune("path", 2)
+        gpu.softmax_tp_tune("block_map", 128)
+        gpu.softmax_tp_tune("unroll_map", 1)
+        xh = workloads.f32_to_f16_bits(x).reshape(x.shape)
+        for tiles in (1, 2, 5):
+            gpu.softmax_tp_tune("tiles_map", tiles)
+            for name, tol in ALGOS_F32:
+                _check(oracle_mod, x, _run(getattr(gpu, name), x, x_off=1, y_off=1), tol)
+            _check(oracle_mod, xb, _run(gpu.softmax2p_bf16io, xb), TOL_BF16, bf16=True)
+            _check(oracle_mod, xh, _run(gpu.softmax3p_recompute_f16io, xh), TOL_F16, f16=True)
+        gpu.softmax_tp_tune("unroll_map", 2)               # 128 threads come with one access only
+        with pytest.raises(gpu.SoftmaxTpError):
+            _run(gpu.softmax2p_f32, x)
     finally:
         gpu.softmax_tp_tune_reset()
 

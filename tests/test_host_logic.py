@@ -80,7 +80,7 @@ def test_planner_on_the_benchmark_configurations(B):
     assert plans[3].nt_first_load == 1 and plans[2].nt_first_load == 0
     # read-only passes: two workgroups of 256 threads per CU; read-write passes: one round each
     assert (plans[3].reduce.block, plans[3].reduce.unroll, plans[3].reduce.chunks) == (256, 4, 512)
-    assert (plans[3].map.block, plans[3].map.unroll, plans[3].map.chunk_vecs) == (512, 2, 1024)
+    assert (plans[3].map.block, plans[3].map.unroll, plans[3].map.chunk_vecs) == (128, 1, 256)
     assert (plans[2].map.block, plans[2].map.chunk_vecs, plans[2].reduce.chunks) == (256, 512, 8)
     for (rows, n, s), p in zip(CONFIGS, plans):
         if p.path != 2:
@@ -160,7 +160,7 @@ def test_tuning_keys(B):
             B.softmax_tp_tune(key, bad)
     B.softmax_tp_tune_reset()
     assert B.softmax_tp_plan(2, 10_000_000).map.block == 256     # short arrays: smaller workgroups
-    assert B.softmax_tp_plan(1, 1 << 28).map.block == 512
+    assert B.softmax_tp_plan(1, 1 << 28).map.block == 128
 
 
 def test_constants_header_is_what_the_generator_writes():
