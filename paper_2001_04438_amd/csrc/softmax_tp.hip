@@ -154,7 +154,9 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
     // four 16-byte loads in flight (8 MiB over the chip), stream fastest; more waves or deeper
     // queues only add contention at the memory channels.
     {
-        const int block = g_tune.block_reduce ? (int)g_tune.block_reduce : 256;
+        // (16-bit elements: twice the waves, these passes being bound by arithmetic there)
+        const int block = g_tune.block_reduce ? (int)g_tune.block_reduce
+                                              : (elem_bytes == 2 ? 512 : 256);
         const int unroll = g_tune.unroll_reduce ? (int)g_tune.unroll_reduce : 4;
         const int64_t target = g_tune.target_reduce ? g_tune.target_reduce : kTargetReduce;
         int64_t per_row = (target + rows - 1) / rows;
