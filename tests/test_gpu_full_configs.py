@@ -74,3 +74,24 @@ def test_full_size_bf16(gpu, oracle_mod):
     print(f"cfg5: max_rel_err={c.max_rel_err:.3e} row_sum_dev={c.max_row_sum_dev:.3e}", flush=True)
     assert c.n_total == x.size and c.ok(), c.as_dict()
     assert c.max_row_sum_dev <= 2e-2
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+def test_full_size_16bit_long_vector(gpu, oracle_mod, fmt):
+    """The values of config 4 narrowed to 16 bits: 2^28 elements through the chunk path in the
+    shapes used beyond the caches (16-bit read-only passes, one access per lane in pass 2)."""
+    x32 = workloads.make("cfg4")
+    rows, n = x32.shape
+    if fmt == "bf16":
+        x, fn, tol, kw = workloads.f32_to_bf16_bits(x32), gpu.softmax2p_bf16io, 1e-2, {"bf16": True}
+    else:
+        x, fn, tol, kw = workloads.f32_to_f16_bits(x32), gpu.softmax2p_f16io, 5e-4, {"f16": True}
+    x = x.reshape(rows, n)
+    del x32
+    plan = gpu.softmax_tp_plan(rows, n, 2)
+    assert plan.path == 2 and plan.map.block == 128 and plan.reduce.block == 512
+    y = _run(fn, x)
+    c = oracle_mod.compare(x, y, tol, **kw)
+    print(f"cfg4 as {fmt}: max_rel_err={c.max_rel_err:.3e} normal={c.n_normal}", flush=True)
+    assert c.n_total == x.size and c.ok(), c.as_dict()
+    assert c.n_normal > 1000
