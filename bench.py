@@ -334,7 +334,15 @@ def main():
             "vs_recompute": head["variants"]["softmax3p_recompute"]["ms_per_step"] / two["ms_per_step"],
             "vs_reload": head["variants"]["softmax3p_reload"]["ms_per_step"] / two["ms_per_step"]}
     if not args.quick:
-        result["calibration"] = calibration(torch, B, args.steps, args.warmup)
+        cal = calibration(torch, B, args.steps, args.warmup)
+        result["calibration"] = cal
+        if "pass2_ms" in head and elems * s == 1 << 30:
+            # each pass next to the plain stream of its kind at the same size (1 GiB), as the paper
+            # sets its passes next to STREAM Copy / Scale (Section 6.4)
+            result["vs_calibration"] = {
+                "pass1_over_stream_read": cal["read"]["ms"] / head["pass1_ms"]["avg"],
+                "pass2_over_stream_copy": cal["copy"]["ms"] / head["pass2_ms"]["avg"],
+                "call_over_read_plus_copy": (cal["read"]["ms"] + cal["copy"]["ms"]) / two["ms_per_step"]}
         others = {}
         for name in ("cfg2", "cfg3", "cfg4", "cfg5", "cfg5_f16"):
             if name == args.workload:
