@@ -194,3 +194,29 @@ def test_fp32_extexp_accuracy_on_the_host(tmp_path):
     out = subprocess.run([str(exe), "-100000", "100000", "4001", threads], check=True,
                          capture_output=True, text=True).stdout.split()
     assert int(out[4]) == 0 and 0.70 < float(out[2]) and float(out[3]) < 1.43
+
+
+def test_header_is_plain_c_and_cxx(tmp_path):
+    """include/softmax_tp.h must be usable from C and from C++ without any HIP header, and a C
+    program must link against the built library through it."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    inc = os.path.join(root, "include")
+    lib_dir = os.path.join(root, "paper_2001_04438_amd")
+    src = tmp_path / "use_header.c"
+    src.write_text(
+        '#include "softmax_tp.h"\n#include <stdio.h>\n'
+        "int main(void) {\n"
+        "    softmax_tp_plan_t p;\n"
+        "    int rc = softmax_tp_plan(1, 268435456, 4, 1, &p);\n"
+        '    printf("%d %d %d %d\\n", rc, p.path, p.launches, softmax2p_f32(0, 0, 0, 5, 0));\n'
+        '    printf("%s\\n", softmax_tp_strerror(TP_ERR_ALIGN));\n'
+        "    return rc;\n}\n")
+    for compiler, std in (("gcc", "-std=c99"), ("g++", "-std=c++11")):
+        subprocess.run([compiler, std, "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-x",
+                        "c" if compiler == "gcc" else "c++", "-I", inc, str(src)], check=True)
+    exe = tmp_path / "use_header"
+    subprocess.run(["gcc", "-std=c99", "-I", inc, "-o", str(exe), str(src), "-L", lib_dir,
+                    "-l:libsoftmax_tp.so", "-Wl,-rpath," + lib_dir], check=True)
+    out = subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout.split("\n")
+    assert out[0] == "0 2 3 0" and out[1].startswith("pointer")
