@@ -195,7 +195,7 @@ typedef struct {
                               2: rows cut into chunks, one launch per pass + small merge launches */
     int32_t vector_elems;  /* elements per access: 4 (fp32) / 8 (bf16), or 1 when unaligned */
     int32_t launches;      /* kernel launches of the Two-Pass call */
-    int32_t merge_kernel;  /* path 2: 1 if a row has more than 64 chunk partials, which a small
+    int32_t merge_kernel;  /* path 2: 1 if a row has more than 128 chunk partials, which a small
                               kernel of its own then merges; 0 if the next pass folds them itself */
     int32_t nt_first_load; /* path 2: 1 if even the first read of x carries the non-temporal hint
                               (input too large for any cache to help the second read) */
@@ -235,9 +235,15 @@ TP_API int softmax_tp_tune(const char *key, int64_t value);
 
 /*
  * Allocates (or grows) the workspace a later softmax call with this shape on this stream
- * would need, so that the call itself does not allocate.  Shapes on the rows path need none.
- * After it, a softmax call on that stream consists of kernel launches only (no allocation,
- * no memset, no host synchronisation) and can be captured into a HIP graph and replayed.
+ * would need, so that the call itself does not allocate: the largest any entry point asks for
+ * with this shape, whether or not x and y are congruent modulo 16 bytes, the pass-level entry
+ * points included.  Shapes on the rows path need none.  After it, a softmax call on that
+ * stream consists of kernel launches only (no allocation, no memset, no host
+ * synchronisation) and can be captured into a HIP graph and replayed.
+ * A stream has one workspace.  A call (or reserve) that needs more than the stream holds
+ * frees the old buffer, which waits for the device, and allocates a larger one: a graph
+ * captured earlier on that stream still points at the freed buffer and must be captured
+ * again.  Reserve the largest shape first, or capture after the last reserve.
  */
 TP_API int softmax_tp_reserve(int64_t rows, int64_t n, int32_t elem_bytes, void *stream);
 

@@ -245,9 +245,16 @@ static int workspace(hipStream_t st, size_t bytes, float **out)
 // launching
 // ===========================================================================
 
-static int launch_status()
+// Launches through hipLaunchKernel and reports that call's own return value.  The thread's
+// "last error" is neither consulted nor cleared: it may hold the result of an earlier call of
+// the caller's (an event query that was not ready, a failed allocation), which says nothing
+// about this launch and is the caller's to read.
+template <class... KArgs>
+static int launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t st,
+                  typename std::common_type<KArgs>::type... args)
 {
-    const hipError_t e = hipGetLastError();
+    void *ptrs[] = {(void *)&args...};
+    const hipError_t e = hipLaunchKernel((const void *)kernel, grid, block, ptrs, 0, st);
     return e == hipSuccess ? TP_OK : (int)e;
 }
 
@@ -285,8 +292,7 @@ static int with_shape(const softmax_tp_shape_t &s, F &&f)
         if constexpr (sizeof(typename IO::elem) == 2 && UU == 8) {           \
             return TP_ERR_TUNING;                                            \
         } else {                                                             \
-            f(ic<B>{}, ic<UU>{});                                            \
-            return launch_status();                                          \
+            return f(ic<B>{}, ic<UU>{});                                     \
         }
     switch (s.block * 16 + s.unroll) {
         TP_CASE(128, 1)
@@ -311,33 +317,22 @@ static int run_rows(Algo algo, const softmax_tp_plan_t &plan, const typename IO:
     if (plan.rows.block == kWave) {  // short rows: a wave per row
         const dim3 wgrid((uint32_t)((rows + kWavesPerGroup - 1) / kWavesPerGroup));
         const dim3 wblock(kWave * kWavesPerGroup);
-#define TP_WAVES(UU)                                                                          \
-    do {                                                                                      \
-        if (algo == kTwoPass)                                                                 \
-            hipLaunchKernelGGL((waves_2p<IO, UU>), wgrid, wblock, 0, st, x, y, n, rows);      \
-        else if (algo == kRecompute)                                                          \
-            hipLaunchKernelGGL((waves_3p_recompute<IO, UU>), wgrid, wblock, 0, st, x, y, n,   \
-                               rows);                                                         \
-        else                                                                                  \
-            hipLaunchKernelGGL((waves_3p_reload<IO, UU>), wgrid, wblock, 0, st, x, y, n,      \
-                               rows);                                                         \
-    } while (0)
-        if (plan.rows.unroll == 2)
-            TP_WAVES(2);
-        else
-            TP_WAVES(4);
-#undef TP_WAVES
-        return launch_status();
+        auto waves = [&](auto U) {
+            if (algo == kTwoPass)
+                return launch(waves_2p<IO, TP_U>, wgrid, wblock, st, x, y, n, rows);
+            if (algo == kRecompute)
+                return launch(waves_3p_recompute<IO, TP_U>, wgrid, wblock, st, x, y, n, rows);
+            return launch(waves_3p_reload<IO, TP_U>, wgrid, wblock, st, x, y, n, rows);
+        };
+        return plan.rows.unroll == 2 ? waves(ic<2>{}) : waves(ic<4>{});
     }
     const dim3 grid((uint32_t)rows);
     return with_shape<IO>(plan.rows, [&](auto B, auto U) {
         if (algo == kTwoPass)
-            hipLaunchKernelGGL((rows_2p<IO, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y, n);
-        else if (algo == kRecompute)
-            hipLaunchKernelGGL((rows_3p_recompute<IO, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y,
-                               n);
-        else
-            hipLaunchKernelGGL((rows_3p_reload<IO, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y, n);
+            return launch(rows_2p<IO, TP_B, TP_U>, grid, dim3(TP_B), st, x, y, n);
+        if (algo == kRecompute)
+            return launch(rows_3p_recompute<IO, TP_B, TP_U>, grid, dim3(TP_B), st, x, y, n);
+        return launch(rows_3p_reload<IO, TP_B, TP_U>, grid, dim3(TP_B), st, x, y, n);
     });
 }
 
@@ -352,17 +347,13 @@ static int run_2p_pass1(const softmax_tp_plan_t &plan, const typename IO::elem *
     const bool nt = plan.nt_first_load != 0;
     int rc = with_shape<IO>(plan.reduce, [&](auto B, auto U) {
         if (nt)
-            hipLaunchKernelGGL((chunk_2p_pass1<IO, TP_B, TP_U, true>), grid, dim3(TP_B), 0, st, x, a,
-                               partial);
-        else
-            hipLaunchKernelGGL((chunk_2p_pass1<IO, TP_B, TP_U, false>), grid, dim3(TP_B), 0, st, x,
-                               a, partial);
+            return launch(chunk_2p_pass1<IO, TP_B, TP_U, true>, grid, dim3(TP_B), st, x, a, partial);
+        return launch(chunk_2p_pass1<IO, TP_B, TP_U, false>, grid, dim3(TP_B), st, x, a, partial);
     });
     if (rc != TP_OK || !merged)
         return rc;
-    hipLaunchKernelGGL(merge_pairs_kernel, dim3((uint32_t)rows), dim3(kMergeBlock), 0, st, partial,
-                       (int)plan.reduce.chunks, merged);
-    return launch_status();
+    return launch(merge_pairs_kernel, dim3((uint32_t)rows), dim3(kMergeBlock), st, partial,
+                  (int)plan.reduce.chunks, merged);
 }
 
 template <class IO>
@@ -373,9 +364,29 @@ static int run_2p_pass2(const softmax_tp_plan_t &plan, const typename IO::elem *
     const ChunkArgs a = chunk_args(n, plan.map, rows, pass_reversed(1));
     const dim3 grid = chunk_grid(rows, plan.map);
     return with_shape<IO>(plan.map, [&](auto B, auto U) {
-        hipLaunchKernelGGL((chunk_2p_pass2<IO, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y, a, pairs,
-                           npairs);
+        return launch(chunk_2p_pass2<IO, TP_B, TP_U>, grid, dim3(TP_B), st, x, y, a, pairs, npairs);
     });
+}
+
+// Bytes of partial results the Two-Pass chunk path needs: one pair per chunk and, when a
+// merge launch is planned, one more per row.
+static int64_t two_pass_scratch_bytes(const softmax_tp_plan_t &plan, int64_t rows)
+{
+    return (rows * plan.reduce.chunks + (plan.merge_kernel ? rows : 0)) * (int64_t)sizeof(float2);
+}
+
+// The Two-Pass chunk path on a buffer for its partial results (two_pass_scratch_bytes of it).
+template <class IO>
+static int run_chunks_2p_on(float *ws, const softmax_tp_plan_t &plan, const typename IO::elem *x,
+                            typename IO::elem *y, int64_t rows, int64_t n, hipStream_t st)
+{
+    float2 *partial = (float2 *)ws;
+    float2 *merged = plan.merge_kernel ? partial + rows * plan.reduce.chunks : nullptr;
+    const int rc = run_2p_pass1<IO>(plan, x, rows, n, st, partial, merged);
+    if (rc != TP_OK)
+        return rc;
+    return merged ? run_2p_pass2<IO>(plan, x, y, rows, n, st, merged, 1)
+                  : run_2p_pass2<IO>(plan, x, y, rows, n, st, partial, (int)plan.reduce.chunks);
 }
 
 template <class IO>
@@ -383,16 +394,10 @@ static int run_chunks_2p(const softmax_tp_plan_t &plan, const typename IO::elem 
                          typename IO::elem *y, int64_t rows, int64_t n, hipStream_t st)
 {
     float *ws = nullptr;
-    int rc = workspace(st, (size_t)plan.workspace_bytes, &ws);
+    const int rc = workspace(st, (size_t)plan.workspace_bytes, &ws);
     if (rc != TP_OK)
         return rc;
-    float2 *partial = (float2 *)ws;
-    float2 *merged = plan.merge_kernel ? partial + rows * plan.reduce.chunks : nullptr;
-    rc = run_2p_pass1<IO>(plan, x, rows, n, st, partial, merged);
-    if (rc != TP_OK)
-        return rc;
-    return merged ? run_2p_pass2<IO>(plan, x, y, rows, n, st, merged, 1)
-                  : run_2p_pass2<IO>(plan, x, y, rows, n, st, partial, (int)plan.reduce.chunks);
+    return run_chunks_2p_on<IO>(ws, plan, x, y, rows, n, st);
 }
 
 template <class IO>
@@ -418,17 +423,15 @@ static int run_chunks_3p(Algo algo, const softmax_tp_plan_t &plan, const typenam
         const ChunkArgs a = chunk_args(n, plan.reduce, rows, pass_reversed(0));
         rc = with_shape<IO>(plan.reduce, [&](auto B, auto U) {
             if (nt)
-                hipLaunchKernelGGL((chunk_max<IO, TP_B, TP_U, true>), rgrid, dim3(TP_B), 0, st, x, a,
-                                   pmax);
-            else
-                hipLaunchKernelGGL((chunk_max<IO, TP_B, TP_U, false>), rgrid, dim3(TP_B), 0, st, x,
-                                   a, pmax);
+                return launch(chunk_max<IO, TP_B, TP_U, true>, rgrid, dim3(TP_B), st, x, a, pmax);
+            return launch(chunk_max<IO, TP_B, TP_U, false>, rgrid, dim3(TP_B), st, x, a, pmax);
         });
         if (rc != TP_OK)
             return rc;
         if (nmax > fold_max()) {
-            hipLaunchKernelGGL(merge_max_kernel, merge_grid, merge_block, 0, st, pmax, nmax, rowmax);
-            if ((rc = launch_status()) != TP_OK)
+            rc = launch(merge_max_kernel, merge_grid, merge_block, st, (const float *)pmax, nmax,
+                        rowmax);
+            if (rc != TP_OK)
                 return rc;
             maxes = rowmax;
             nmax = 1;
@@ -442,26 +445,25 @@ static int run_chunks_3p(Algo algo, const softmax_tp_plan_t &plan, const typenam
         nsum = (int)plan.reduce.chunks;
         rc = with_shape<IO>(plan.reduce, [&](auto B, auto U) {
             if (nt)
-                hipLaunchKernelGGL((chunk_sumexp<IO, TP_B, TP_U, true>), rgrid, dim3(TP_B), 0, st, x,
-                                   a, maxes, nmax, psum);
-            else
-                hipLaunchKernelGGL((chunk_sumexp<IO, TP_B, TP_U, false>), rgrid, dim3(TP_B), 0, st,
-                                   x, a, maxes, nmax, psum);
+                return launch(chunk_sumexp<IO, TP_B, TP_U, true>, rgrid, dim3(TP_B), st, x, a, maxes,
+                              nmax, psum);
+            return launch(chunk_sumexp<IO, TP_B, TP_U, false>, rgrid, dim3(TP_B), st, x, a, maxes,
+                          nmax, psum);
         });
     } else {
         const ChunkArgs a = chunk_args(n, plan.mapsum, rows, pass_reversed(1));
         const dim3 grid = chunk_grid(rows, plan.mapsum);
         nsum = (int)plan.mapsum.chunks;
         rc = with_shape<IO>(plan.mapsum, [&](auto B, auto U) {
-            hipLaunchKernelGGL((chunk_expstore<IO, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y, a,
-                               maxes, nmax, psum);
+            return launch(chunk_expstore<IO, TP_B, TP_U>, grid, dim3(TP_B), st, x, y, a, maxes, nmax,
+                          psum);
         });
     }
     if (rc != TP_OK)
         return rc;
     if (nsum > fold_max()) {
-        hipLaunchKernelGGL(merge_sum_kernel, merge_grid, merge_block, 0, st, psum, nsum, rowsum);
-        if ((rc = launch_status()) != TP_OK)
+        rc = launch(merge_sum_kernel, merge_grid, merge_block, st, (const float *)psum, nsum, rowsum);
+        if (rc != TP_OK)
             return rc;
         sums = rowsum;
         nsum = 1;
@@ -471,13 +473,12 @@ static int run_chunks_3p(Algo algo, const softmax_tp_plan_t &plan, const typenam
     const dim3 grid = chunk_grid(rows, plan.map);
     if (algo == kRecompute)
         return with_shape<IO>(plan.map, [&](auto B, auto U) {
-            hipLaunchKernelGGL((chunk_expscale<IO, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y, a,
-                               maxes, nmax, sums, nsum);
+            return launch(chunk_expscale<IO, TP_B, TP_U>, grid, dim3(TP_B), st, x, y, a, maxes, nmax,
+                          sums, nsum);
         });
     const typename IO::elem *yc = y;
     return with_shape<IO>(plan.map, [&](auto B, auto U) {
-        hipLaunchKernelGGL((chunk_scale<IO, TP_B, TP_U>), grid, dim3(TP_B), 0, st, yc, y, a, sums,
-                           nsum, 0.f);
+        return launch(chunk_scale<IO, TP_B, TP_U>, grid, dim3(TP_B), st, yc, y, a, sums, nsum, 0.f);
     });
 }
 
@@ -584,8 +585,7 @@ static int launch_onchip(int algo, const typename IO::elem *x, typename IO::elem
     if (rc != TP_OK)
         return rc;
     const int64_t grid = rows < resident ? rows : resident;
-    hipLaunchKernelGGL(kernel, dim3((uint32_t)grid), dim3(B), 0, st, x, y, n, rows);
-    return launch_status();
+    return launch(kernel, dim3((uint32_t)grid), dim3(B), st, x, y, n, rows);
 }
 
 template <class IO, int B, int U>
@@ -768,13 +768,8 @@ static int run_extexp(bool hw, const float *x, float *m, float *e, int64_t count
     int64_t blocks = (count + 255) / 256;
     if (blocks > 65536)
         blocks = 65536;
-    if (hw)
-        hipLaunchKernelGGL(extexp_kernel<true>, dim3((uint32_t)blocks), dim3(256), 0,
-                           (hipStream_t)stream, x, m, e, count);
-    else
-        hipLaunchKernelGGL(extexp_kernel<false>, dim3((uint32_t)blocks), dim3(256), 0,
-                           (hipStream_t)stream, x, m, e, count);
-    return launch_status();
+    return launch(hw ? extexp_kernel<true> : extexp_kernel<false>, dim3((uint32_t)blocks), dim3(256),
+                  (hipStream_t)stream, x, m, e, count);
 }
 
 int softmax_tp_extexp_f32(const float *x, float *m, float *e, int64_t count, void *stream)
@@ -841,13 +836,12 @@ int softmax_tp_stream_read_f32(const float *x, float *sink, int64_t count, void 
     const ChunkArgs a = chunk_args(count, plan.reduce, 1, false);
     const dim3 grid = chunk_grid(1, plan.reduce);
     rc = with_shape<F32x4>(plan.reduce, [&](auto B, auto U) {
-        hipLaunchKernelGGL((chunk_read<F32x4, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, a, ws);
+        return launch(chunk_read<F32x4, TP_B, TP_U>, grid, dim3(TP_B), st, x, a, ws);
     });
     if (rc != TP_OK)
         return rc;
-    hipLaunchKernelGGL(merge_sum_kernel, dim3(1), dim3(kMergeBlock), 0, st, ws,
-                       (int)plan.reduce.chunks, sink);
-    return launch_status();
+    return launch(merge_sum_kernel, dim3(1), dim3(kMergeBlock), st, (const float *)ws,
+                  (int)plan.reduce.chunks, sink);
 }
 
 int softmax_tp_stream_copy_f32(const float *x, float *y, int64_t count, void *stream)
@@ -864,10 +858,10 @@ int softmax_tp_stream_copy_f32(const float *x, float *y, int64_t count, void *st
     const dim3 grid = chunk_grid(1, plan.map);
     if (vec)
         return with_shape<F32x4>(plan.map, [&](auto B, auto U) {
-            hipLaunchKernelGGL((chunk_copy<F32x4, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y, a);
+            return launch(chunk_copy<F32x4, TP_B, TP_U>, grid, dim3(TP_B), st, x, y, a);
         });
     return with_shape<F32x1>(plan.map, [&](auto B, auto U) {
-        hipLaunchKernelGGL((chunk_copy<F32x1, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y, a);
+        return launch(chunk_copy<F32x1, TP_B, TP_U>, grid, dim3(TP_B), st, x, y, a);
     });
 }
 
@@ -886,12 +880,11 @@ int softmax_tp_stream_scale_f32(const float *x, float *y, float scale, int64_t c
     const float *none = nullptr;
     if (vec)
         return with_shape<F32x4>(plan.map, [&](auto B, auto U) {
-            hipLaunchKernelGGL((chunk_scale<F32x4, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y, a,
-                               none, 0, scale);
+            return launch(chunk_scale<F32x4, TP_B, TP_U>, grid, dim3(TP_B), st, x, y, a, none, 0,
+                          scale);
         });
     return with_shape<F32x1>(plan.map, [&](auto B, auto U) {
-        hipLaunchKernelGGL((chunk_scale<F32x1, TP_B, TP_U>), grid, dim3(TP_B), 0, st, x, y, a, none,
-                           0, scale);
+        return launch(chunk_scale<F32x1, TP_B, TP_U>, grid, dim3(TP_B), st, x, y, a, none, 0, scale);
     });
 }
 
@@ -946,12 +939,24 @@ int softmax_tp_tune(const char *key, int64_t value)
 
 int softmax_tp_reserve(int64_t rows, int64_t n, int32_t elem_bytes, void *stream)
 {
-    softmax_tp_plan_t plan;
-    int rc = make_plan(rows, n, elem_bytes, true, 0, &plan);
-    if (rc != TP_OK || plan.workspace_bytes == 0)
-        return rc;
+    // The largest workspace any entry point can ask for with this shape: x and y congruent
+    // modulo 16 bytes or not (element-wise accesses make more, shorter chunks in the pass that
+    // stores and sums), and the chunk path forced, as the pass-level entry points do for shapes
+    // whose full call takes the rows path.
+    int64_t bytes = 0;
+    for (int congruent = 0; congruent < 2; ++congruent)
+        for (int force_path = 0; force_path <= 2; force_path += 2) {
+            softmax_tp_plan_t plan;
+            const int rc = make_plan(rows, n, elem_bytes, congruent != 0, force_path, &plan);
+            if (rc != TP_OK)
+                return rc;
+            if (plan.workspace_bytes > bytes)
+                bytes = plan.workspace_bytes;
+        }
+    if (bytes == 0)
+        return TP_OK;
     float *ws = nullptr;
-    return workspace((hipStream_t)stream, (size_t)plan.workspace_bytes, &ws);
+    return workspace((hipStream_t)stream, (size_t)bytes, &ws);
 }
 
 int softmax_tp_release(void)

@@ -327,6 +327,52 @@ def test_nan_poisons_only_its_row(gpu):
         assert np.isfinite(np.delete(y, 5, axis=0)).all()
 
 
+def test_infinity_poisons_only_its_row(gpu):
+    """Infinite inputs are outside the contract (the header says so); what happens is pinned
+    all the same: the range reduction turns an infinity into NaN, so the row that holds it comes
+    out NaN, as with a NaN input, and no other row is touched."""
+    base = workloads.cfg2(rows=34, n=3000)
+    for bad in (-np.inf, np.inf):
+        x = base.copy()
+        x[7, 1234] = bad
+        for name in ("softmax2p_f32", "softmax3p_recompute_f32", "softmax3p_reload_f32",
+                     "softmax2p_onchip_f32", "softmax3p_onchip_f32"):
+            y = _run(getattr(gpu, name), x)
+            assert np.isnan(y[7]).all(), (name, bad)
+            assert np.isfinite(np.delete(y, 7, axis=0)).all(), (name, bad)
+        xb = workloads.f32_to_bf16_bits(x).reshape(x.shape)
+        xh = workloads.f32_to_f16_bits(x).reshape(x.shape)
+        for name, xs, conv in (("softmax2p_bf16io", xb, workloads.bf16_bits_to_f32),
+                               ("softmax2p_onchip_bf16io", xb, workloads.bf16_bits_to_f32),
+                               ("softmax2p_f16io", xh, workloads.f16_bits_to_f32),
+                               ("softmax2p_onchip_f16io", xh, workloads.f16_bits_to_f32)):
+            y = conv(_run(getattr(gpu, name), xs)).reshape(x.shape)
+            assert np.isnan(y[7]).all(), (name, bad)
+            assert np.isfinite(np.delete(y, 7, axis=0)).all(), (name, bad)
+
+
+def test_a_stale_hip_error_of_the_callers_is_not_reported_as_ours(gpu, oracle_mod):
+    """An earlier failed HIP call of the caller's leaves an error behind in the thread.  The
+    library reports what its own launches return, so the call succeeds and every pass runs."""
+    import ctypes
+    import torch
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipMalloc.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_size_t]
+    x = workloads.cfg3(rows=2, n=1_500_000)
+    rows, n = x.shape
+    xd = torch.from_numpy(x.reshape(-1)).cuda()
+    for name, tol in ALGOS_F32:                       # three to five launches each
+        yd = torch.full_like(xd, -7.0)
+        torch.cuda.synchronize()
+        p = ctypes.c_void_p()
+        assert hip.hipMalloc(ctypes.byref(p), 1 << 60) != 0     # refused: far beyond the device
+        rc = getattr(gpu.lib(), name)(xd.data_ptr(), yd.data_ptr(), rows, n, None)
+        hip.hipGetLastError()                          # leave no error behind for torch to find
+        assert rc == 0, (name, rc)
+        torch.cuda.synchronize()
+        _check(oracle_mod, x, yd.cpu().numpy().reshape(rows, n), tol)
+
+
 # ---------------------------------------------------------------------------
 # on-chip variant (row kept in registers between the passes)
 # ---------------------------------------------------------------------------
@@ -653,6 +699,52 @@ def test_capture_into_a_graph_and_replay(gpu, oracle_mod):
             if trial == 2:
                 _check(oracle_mod, host, y.cpu().numpy().reshape(rows, n), tol)
         del graph
+
+
+def test_reserve_covers_incongruent_pointers_and_pass_level_calls(gpu, oracle_mod):
+    """x and y one element apart modulo 16 bytes: the element-wise kernels cut the storing pass
+    into more chunks and need a larger workspace; the pass-level entry points use the chunk
+    kernels for shapes whose full call needs no workspace.  One reserve must cover all of it,
+    or the call would allocate under capture and the capture would fail."""
+    import torch
+    side = torch.cuda.Stream()
+    rows, n = 1000, 100_000
+    # beyond the smallest buffer the library ever allocates (64 KiB), and only when incongruent
+    assert (gpu.softmax_tp_plan(rows, n, 4, False).workspace_bytes > 65536
+            > gpu.softmax_tp_plan(rows, n, 4, True).workspace_bytes)
+    host = workloads.cfg2(rows=rows, n=n)
+    xbuf = torch.empty(rows * n + 8, dtype=torch.float32, device="cuda")
+    ybuf = torch.full((rows * n + 8,), -7.0, dtype=torch.float32, device="cuda")
+    x, y = xbuf[1:1 + rows * n], ybuf[2:2 + rows * n]
+    x.copy_(torch.from_numpy(host.reshape(-1)))
+    gpu.softmax_tp_release()
+    gpu.softmax_tp_reserve(rows, n, 4, stream=side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        gpu.softmax3p_reload_f32(x, y, rows, n)
+    graph.replay()
+    torch.cuda.synchronize()
+    _check(oracle_mod, host, y.cpu().numpy().reshape(rows, n), TOL_3P)
+    del graph
+    # a rows-path shape through the pass-level entry point
+    rows, n = 300, 5000
+    assert gpu.softmax_tp_plan(rows, n).path == 1
+    host = workloads.cfg2(rows=rows, n=n)
+    x = torch.from_numpy(host.reshape(-1)).cuda()
+    y = torch.empty_like(x)
+    pairs = torch.empty(2 * rows, dtype=torch.float32, device="cuda")
+    gpu.softmax_tp_release()
+    gpu.softmax_tp_reserve(rows, n, 4, stream=side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        gpu.softmax2p_f32_pass1(x, pairs, rows, n)
+        gpu.softmax2p_f32_pass2(x, pairs, y, rows, n)
+    graph.replay()
+    torch.cuda.synchronize()
+    _check(oracle_mod, host, y.cpu().numpy().reshape(rows, n), TOL_2P)
+    del graph
 
 
 def test_calibration_streams(gpu):
