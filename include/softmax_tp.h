@@ -51,6 +51,7 @@ extern "C" {
 #define TP_ERR_TOO_LARGE (-3) /* rows * n * element size overflows, or rows / chunks exceed the grid limit */
 #define TP_ERR_ALIGN (-4)     /* a pointer is not aligned to the element size */
 #define TP_ERR_TUNING (-5)    /* unknown tuning key or value out of range */
+#define TP_ERR_SCRATCH (-6)   /* softmax2p_f32_static: the shape needs more than TP_STATIC_SCRATCH_BYTES */
 
 /*
  * Algorithm 3 (Section 4), fp32 in and out.  Pass 1 evaluates every e^x as a pair
@@ -142,6 +143,27 @@ TP_API int softmax3p_onchip_bf16io(const uint16_t *x, uint16_t *y, int64_t rows,
                                    void *stream);
 TP_API int softmax3p_onchip_f16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n,
                                   void *stream);
+
+/*
+ * softmax2p_f32 for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same kernels, launch plan and results (bit for bit)
+ * as softmax2p_f32, but the chunk path's partial results (one 8-byte pair per chunk, plus one
+ * per row when a merge launch is planned) go to a fixed array of TP_STATIC_SCRATCH_BYTES that
+ * is part of the library's device code instead of the allocated workspace: the call makes no
+ * hipMalloc / hipFree, no memset, no synchronisation, needs no softmax_tp_reserve, and its
+ * first call on a device only looks the array's address up.  Each GPU the library runs on
+ * holds that array until the process ends.
+ * A shape whose partial results do not fit returns TP_ERR_SCRATCH before anything is
+ * launched.  It fits when rows * (reduce.chunks + 1) <= 32768 (softmax_tp_plan reports
+ * reduce.chunks): with the default tuning that is every chunk-path input of up to 32768 rows
+ * of at most 1 GiB each; the one-workgroup-per-row path needs no scratch at any row count.
+ * All calls on one GPU share the array, whatever their stream: two calls whose execution
+ * overlaps on one GPU race on it and give wrong results.  Calls that follow one another
+ * on one stream are safe, and nothing needs clearing between them: every slot a call reads it
+ * has written itself first.
+ */
+#define TP_STATIC_SCRATCH_BYTES (256 * 1024)
+TP_API int softmax2p_f32_static(const float *x, float *y, int64_t rows, int64_t n, void *stream);
 
 /* ----- pieces of the path, exported for tests and for per-pass timing ----- */
 

@@ -34,6 +34,7 @@ ENTRY_POINTS = {
     "softmax3p_onchip_f32": [_vp, _vp, _i64, _i64, _vp],
     "softmax3p_onchip_bf16io": [_vp, _vp, _i64, _i64, _vp],
     "softmax3p_onchip_f16io": [_vp, _vp, _i64, _i64, _vp],
+    "softmax2p_f32_static": [_vp, _vp, _i64, _i64, _vp],
     "softmax_tp_extexp_f32": [_vp, _vp, _vp, _i64, _vp],
     "softmax_tp_extexp_hw_f32": [_vp, _vp, _vp, _i64, _vp],
     "softmax2p_f32_pass1": [_vp, _vp, _i64, _i64, _vp],
@@ -49,6 +50,8 @@ ENTRY_POINTS = {
 }
 
 TP_ERR_NULL, TP_ERR_NEGATIVE, TP_ERR_TOO_LARGE, TP_ERR_ALIGN, TP_ERR_TUNING = -1, -2, -3, -4, -5
+TP_ERR_SCRATCH = -6
+TP_STATIC_SCRATCH_BYTES = 256 * 1024
 
 
 class Shape(ctypes.Structure):
@@ -209,6 +212,10 @@ def softmax3p_onchip_bf16io(x, y, rows, n, stream=None):
 
 def softmax3p_onchip_f16io(x, y, rows, n, stream=None):
     _softmax("softmax3p_onchip_f16io", x, y, rows, n, stream)
+
+
+def softmax2p_f32_static(x, y, rows, n, stream=None):
+    _softmax("softmax2p_f32_static", x, y, rows, n, stream)
 
 
 def softmax_tp_extexp_f32(x, m, e, count, stream=None):

@@ -888,6 +888,64 @@ int softmax_tp_stream_scale_f32(const float *x, float *y, float scale, int64_t c
     });
 }
 
+// ---- Two-Pass softmax that allocates nothing ------------------------------------------
+//
+// The partial results of the chunk path live in a device array that is part of the library's
+// code object.  Each GPU holds its own copy at its own address; the address is looked up once
+// per device with that device current and kept.  In host code the array's name is only a
+// handle for that lookup, never a pointer to hand to a kernel.
+static __device__ __align__(256) unsigned char scratch[TP_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices];
+
+static int static_scratch(float **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return (int)e;
+    if (dev < 0 || dev >= kMaxDevices)
+        return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess)
+            return (int)e;
+        if (!ptr)
+            return (int)hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = (float *)g_scratch_ptr[dev];
+    return TP_OK;
+}
+
+int softmax2p_f32_static(const float *x, float *y, int64_t rows, int64_t n, void *stream)
+{
+    int rc = check_args(x, y, rows, n, 4);
+    if (rc != TP_OK || rows == 0 || n == 0)
+        return rc;
+    const bool vec = congruent16(x, y);
+    softmax_tp_plan_t plan;
+    if ((rc = make_plan(rows, n, 4, vec, 0, &plan)) != TP_OK)
+        return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if (plan.path == 1)  // one workgroup per row: no partial results outside the workgroup
+        return vec ? run_rows<F32x4>(kTwoPass, plan, x, y, rows, n, st)
+                   : run_rows<F32x1>(kTwoPass, plan, x, y, rows, n, st);
+    if (two_pass_scratch_bytes(plan, rows) > (int64_t)TP_STATIC_SCRATCH_BYTES)
+        return TP_ERR_SCRATCH;
+    // Every slot that pass 2 or the merge reads is written by pass 1 of the same call first, so
+    // nothing has to be cleared, whatever an earlier call left behind.
+    float *ws = nullptr;
+    if ((rc = static_scratch(&ws)) != TP_OK)
+        return rc;
+    return vec ? run_chunks_2p_on<F32x4>(ws, plan, x, y, rows, n, st)
+               : run_chunks_2p_on<F32x1>(ws, plan, x, y, rows, n, st);
+}
+
 int softmax_tp_plan(int64_t rows, int64_t n, int32_t elem_bytes, int32_t congruent,
                     softmax_tp_plan_t *plan)
 {
@@ -987,6 +1045,7 @@ const char *softmax_tp_strerror(int code)
     case TP_ERR_TOO_LARGE: return "problem too large";
     case TP_ERR_ALIGN: return "pointer not aligned to the element size";
     case TP_ERR_TUNING: return "bad tuning key, value or unsupported configuration";
+    case TP_ERR_SCRATCH: return "partial results exceed the static scratch buffer";
     default: return code > 0 ? hipGetErrorString((hipError_t)code) : "unknown error";
     }
 }

@@ -59,6 +59,13 @@ def test_arguments_are_validated_before_any_gpu_call(B):
     assert L.softmax2p_f32_pass2(64, None, 64, 1, 4, None) == B.TP_ERR_NULL
     assert L.softmax2p_f32_pass2(64, 68, 64, 1, 4, None) == B.TP_ERR_ALIGN  # pairs need 8 bytes
     assert L.softmax_tp_stream_copy_f32(None, 64, 5, None) == B.TP_ERR_NULL
+    # the entry point on static scratch: usual checks first, then the size of its partial results
+    assert L.softmax2p_f32_static(None, 64, 1, 4, None) == B.TP_ERR_NULL
+    assert L.softmax2p_f32_static(64, 64, -1, 4, None) == B.TP_ERR_NEGATIVE
+    assert L.softmax2p_f32_static(None, None, 0, 7, None) == 0
+    assert B.softmax_tp_plan(200_000, 100_000).path == 2
+    assert L.softmax2p_f32_static(64, 64, 200_000, 100_000, None) == B.TP_ERR_SCRATCH
+    assert "scratch" in B.strerror(B.TP_ERR_SCRATCH)
     assert L.softmax_tp_plan(1, 1, 3, 1, ctypes.byref(B.Plan())) == B.TP_ERR_TUNING
     assert L.softmax_tp_plan(1, 1, 4, 1, None) == B.TP_ERR_NULL
     assert B.strerror(B.TP_ERR_ALIGN).startswith("pointer")
