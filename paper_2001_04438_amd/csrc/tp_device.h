@@ -9,6 +9,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "extexp.h"
 
 namespace tp {
@@ -52,6 +54,33 @@ __device__ __forceinline__ float exp_nonpos(float d)
     float m, n;
     tp_extexp(d, &m, &n);
     return scale_pow2(m, n);
+}
+
+// ---- the same for the evaluator whose exponent is the bit pattern of z (extexp.h) ----
+
+// Saturating 32-bit subtraction / addition (v_sub_i32 / v_add_i32 with clamp): differences of
+// exponent bit patterns never wrap, whatever the input, so a scale factor is never positive
+// by accident.
+__device__ __forceinline__ int sub_sat(int a, int b) { return __builtin_elementwise_sub_sat(a, b); }
+__device__ __forceinline__ int add_sat(int a, int b) { return __builtin_elementwise_add_sat(a, b); }
+
+// Bit pattern standing for the exponent of the additive identity: below that of every z.
+constexpr int kZIdent = -0x40000000;
+
+__device__ __forceinline__ float exp_nonpos_bits(float d)
+{
+    float m, z;
+    tp_extexp_bits(d, &m, &z);
+    return __builtin_ldexpf(m, sub_sat(tp_float_bits(z), TP_MAGIC_BITS));
+}
+
+template <bool INT_EXP>
+__device__ __forceinline__ float exp_nonpos_as(float d)
+{
+    if constexpr (INT_EXP)
+        return exp_nonpos_bits(d);
+    else
+        return exp_nonpos(d);
 }
 
 // ---------------------------------------------------------------------------
@@ -212,6 +241,7 @@ __device__ __forceinline__ uint32_t bf16_pack(float lo, float hi)  // round to n
 }
 
 struct F32x4 {  // fp32, 16-byte vectors
+    static constexpr bool kIntExp = false;  // which ExtExp evaluator: see extexp.h
     using elem = float;
     using vec = f32x4;
     static constexpr int V = 4;
@@ -230,6 +260,7 @@ struct F32x4 {  // fp32, 16-byte vectors
 };
 
 struct F32x1 {  // fp32, element-wise (x and y not congruent modulo 16 bytes)
+    static constexpr bool kIntExp = false;  // which ExtExp evaluator: see extexp.h
     using elem = float;
     using vec = float;
     static constexpr int V = 1;
@@ -241,6 +272,7 @@ struct F32x1 {  // fp32, element-wise (x and y not congruent modulo 16 bytes)
 };
 
 struct BF16x8 {  // bf16 in and out, 16-byte vectors, fp32 arithmetic
+    static constexpr bool kIntExp = true;  // which ExtExp evaluator: see extexp.h
     using elem = uint16_t;
     using vec = u32x4;
     static constexpr int V = 8;
@@ -267,6 +299,7 @@ struct BF16x8 {  // bf16 in and out, 16-byte vectors, fp32 arithmetic
 };
 
 struct BF16x1 {  // bf16, element-wise
+    static constexpr bool kIntExp = true;  // which ExtExp evaluator: see extexp.h
     using elem = uint16_t;
     using vec = uint16_t;
     static constexpr int V = 1;
@@ -298,6 +331,7 @@ __device__ __forceinline__ uint32_t f16_pack(float lo, float hi)
 }
 
 struct F16x8 {  // fp16 in and out, 16-byte vectors, fp32 arithmetic
+    static constexpr bool kIntExp = true;  // which ExtExp evaluator: see extexp.h
     using elem = uint16_t;
     using vec = u32x4;
     static constexpr int V = 8;
@@ -326,6 +360,7 @@ struct F16x8 {  // fp16 in and out, 16-byte vectors, fp32 arithmetic
 };
 
 struct F16x1 {  // fp16, element-wise
+    static constexpr bool kIntExp = true;  // which ExtExp evaluator: see extexp.h
     using elem = uint16_t;
     using vec = uint16_t;
     static constexpr int V = 1;
@@ -506,8 +541,10 @@ __device__ __forceinline__ float tree_sum(float *v)
 struct PairSum {
     static constexpr bool kWrite = false;
     float m = 0.f, n = kNIdent;
+    // If `e` is given, the group's mantissas are left there scaled to the exponent `n` holds
+    // after the call.
     template <int G>
-    __device__ __forceinline__ void group(const float *f, float *)
+    __device__ __forceinline__ void group(const float *f, float *e)
     {
         float mi[G], ni[G];
         float nmax = n;
@@ -518,10 +555,68 @@ struct PairSum {
         }
         float acc = scale_pow2(m, n - nmax);
 #pragma unroll
-        for (int i = 0; i < G; ++i)
+        for (int i = 0; i < G; ++i) {
             mi[i] = scale_pow2(mi[i], ni[i] - nmax);
+            if (e)
+                e[i] = mi[i];
+        }
         m = acc + tree_sum<G>(mi);
         n = nmax;
+    }
+    __device__ __forceinline__ void finish(float &m_out, float &n_out) const
+    {
+        m_out = m;
+        n_out = n;
+    }
+    // For a caller that keeps the scaled mantissas of a group: the exponent they were scaled
+    // to, and the factor that takes them from there to lambda * 2^(that exponent - n_sum).
+    using token = float;
+    __device__ __forceinline__ token exponent() const { return n; }
+    static __device__ __forceinline__ float factor(float lambda, token g, float n_sum)
+    {
+        return scale_pow2(lambda, g - n_sum);
+    }
+};
+
+// The same on the integer-exponent evaluator (16-bit storage formats): the running exponent
+// is the bit pattern of z, the group maximum an integer maximum, and each rescale one integer
+// subtraction and one v_ldexp_f32.  If `e` is given, the group's mantissas are left there
+// scaled to the exponent in `z` after the call, for a caller that keeps them.
+struct PairSumI {
+    static constexpr bool kWrite = false;
+    float m = 0.f;
+    int z = kZIdent;
+    template <int G>
+    __device__ __forceinline__ void group(const float *f, float *e)
+    {
+        float mi[G], zf[G];
+        int zmax = z;
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            tp_extexp_bits(f[i], &mi[i], &zf[i]);
+            zmax = max(zmax, tp_float_bits(zf[i]));
+        }
+        const float acc = __builtin_ldexpf(m, sub_sat(z, zmax));
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            mi[i] = __builtin_ldexpf(mi[i], sub_sat(tp_float_bits(zf[i]), zmax));
+            if (e)
+                e[i] = mi[i];
+        }
+        m = acc + tree_sum<G>(mi);
+        z = zmax;
+    }
+    // the pair in the float form every merge level above the thread works on
+    __device__ __forceinline__ void finish(float &m_out, float &n_out) const
+    {
+        m_out = m;
+        n_out = (float)sub_sat(z, TP_MAGIC_BITS);
+    }
+    using token = int;
+    __device__ __forceinline__ token exponent() const { return z; }
+    static __device__ __forceinline__ float factor(float lambda, token g, float n_sum)
+    {
+        return __builtin_ldexpf(lambda, sub_sat(g, add_sat(TP_MAGIC_BITS, cvt_i32_sat(n_sum))));
     }
 };
 
@@ -547,6 +642,32 @@ struct PairOut {
     }
 };
 
+struct PairOutI {
+    static constexpr bool kWrite = true;
+    float cs[6];
+    int k;  // the bit pattern z would have for n = n_sum
+    __device__ __forceinline__ PairOutI(float lambda, float n_sum)
+        : k(add_sat(TP_MAGIC_BITS, cvt_i32_sat(n_sum)))
+    {
+        tp_scale_coeffs(lambda, cs);
+    }
+    template <int G>
+    __device__ __forceinline__ void group(const float *f, float *o)
+    {
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            float ml, z;
+            tp_extexp_bits_scaled(f[i], cs, &ml, &z);
+            o[i] = __builtin_ldexpf(ml, sub_sat(tp_float_bits(z), k));
+        }
+    }
+};
+
+template <class IO>
+using PairSumOf = std::conditional_t<IO::kIntExp, PairSumI, PairSum>;
+template <class IO>
+using PairOutOf = std::conditional_t<IO::kIntExp, PairOutI, PairOut>;
+
 // Three-Pass, pass 1: running maximum.
 struct MaxOf {
     static constexpr bool kWrite = false;
@@ -560,7 +681,9 @@ struct MaxOf {
     }
 };
 
-// Three-Pass (recompute), pass 2: sigma += Exp(x - mu).
+// Three-Pass (recompute), pass 2: sigma += Exp(x - mu).  INT_EXP picks the evaluator (all
+// three-pass policies): both families always share one, as in the paper (Section 6.3).
+template <bool INT_EXP>
 struct SumExp {
     static constexpr bool kWrite = false;
     float mu;
@@ -571,13 +694,14 @@ struct SumExp {
         float e[G];
 #pragma unroll
         for (int i = 0; i < G; ++i)
-            e[i] = exp_nonpos(f[i] - mu);
+            e[i] = exp_nonpos_as<INT_EXP>(f[i] - mu);
         s += tree_sum<G>(e);
     }
 };
 
 // Three-Pass (recompute), pass 3: Y_i = lambda * Exp(x - mu), lambda folded into the
 // polynomial as in PairOut so both families pay the same per element.
+template <bool INT_EXP>
 struct ExpScale {
     static constexpr bool kWrite = true;
     float cs[6];
@@ -591,14 +715,21 @@ struct ExpScale {
     {
 #pragma unroll
         for (int i = 0; i < G; ++i) {
-            float ml, ni;
-            tp_extexp_scaled(f[i] - mu, cs, &ml, &ni);
-            o[i] = scale_pow2(ml, ni);
+            if constexpr (INT_EXP) {
+                float ml, z;
+                tp_extexp_bits_scaled(f[i] - mu, cs, &ml, &z);
+                o[i] = __builtin_ldexpf(ml, sub_sat(tp_float_bits(z), TP_MAGIC_BITS));
+            } else {
+                float ml, ni;
+                tp_extexp_scaled(f[i] - mu, cs, &ml, &ni);
+                o[i] = scale_pow2(ml, ni);
+            }
         }
     }
 };
 
 // Three-Pass (reload), pass 2: Y_i = Exp(x - mu), sigma += Y_i.
+template <bool INT_EXP>
 struct ExpStoreSum {
     static constexpr bool kWrite = true;
     float mu;
@@ -609,7 +740,7 @@ struct ExpStoreSum {
         float e[G];
 #pragma unroll
         for (int i = 0; i < G; ++i)
-            e[i] = o[i] = exp_nonpos(f[i] - mu);
+            e[i] = o[i] = exp_nonpos_as<INT_EXP>(f[i] - mu);
         s += tree_sum<G>(e);
     }
 };

@@ -27,10 +27,12 @@ __global__ __launch_bounds__(BLOCK) void rows_2p(const typename IO::elem *x,
 {
     __shared__ float lds[2 * kMaxWaves];
     const Seg<IO> s = make_seg<IO>(x, y, n, blockIdx.x, 0, INT64_MAX / 2);
-    PairSum acc;
+    PairSumOf<IO> acc;
     stream<IO, BLOCK, U, kLoadKeep, kStoreStream>(s, acc);
-    block_pair<BLOCK>(acc.m, acc.n, lds);
-    PairOut out(1.0f / acc.m, acc.n);
+    float m_sum, n_sum;
+    acc.finish(m_sum, n_sum);
+    block_pair<BLOCK>(m_sum, n_sum, lds);
+    PairOutOf<IO> out(1.0f / m_sum, n_sum);
     stream<IO, BLOCK, U, kLoadStream, kStoreStream>(s, out);
 }
 
@@ -43,10 +45,10 @@ __global__ __launch_bounds__(BLOCK) void rows_3p_recompute(const typename IO::el
     MaxOf mx;
     stream<IO, BLOCK, U, kLoadKeep, kStoreStream>(s, mx);
     const float mu = block_max<BLOCK>(mx.mx, lds);
-    SumExp se{mu};
+    SumExp<IO::kIntExp> se{mu};
     stream<IO, BLOCK, U, kLoadKeep, kStoreStream>(s, se);
     const float sigma = block_sum<BLOCK>(se.s, lds);
-    ExpScale es(mu, 1.0f / sigma);
+    ExpScale<IO::kIntExp> es(mu, 1.0f / sigma);
     stream<IO, BLOCK, U, kLoadStream, kStoreStream>(s, es);
 }
 
@@ -59,7 +61,7 @@ __global__ __launch_bounds__(BLOCK) void rows_3p_reload(const typename IO::elem 
     MaxOf mx;
     stream<IO, BLOCK, U, kLoadKeep, kStoreStream>(s, mx);
     const float mu = block_max<BLOCK>(mx.mx, lds);
-    ExpStoreSum ess{mu};
+    ExpStoreSum<IO::kIntExp> ess{mu};
     stream<IO, BLOCK, U, kLoadStream, kStoreKeep>(s, ess);  // y is read back by the next pass
     const float sigma = block_sum<BLOCK>(ess.s, lds);
     // each thread re-reads exactly the vectors it stored itself, so program order suffices
@@ -88,10 +90,12 @@ __global__ __launch_bounds__(kWave *kWavesPerGroup) void waves_2p(const typename
                                                                    int64_t n, int64_t rows)
 {
     TP_WAVE_ROW_PROLOGUE
-    PairSum acc;
+    PairSumOf<IO> acc;
     stream<IO, kWave, U, kLoadKeep, kStoreStream>(s, acc, lane);
-    wave_pair(acc.m, acc.n);
-    PairOut out(1.0f / acc.m, acc.n);
+    float m_sum, n_sum;
+    acc.finish(m_sum, n_sum);
+    wave_pair(m_sum, n_sum);
+    PairOutOf<IO> out(1.0f / m_sum, n_sum);
     stream<IO, kWave, U, kLoadStream, kStoreStream>(s, out, lane);
 }
 
@@ -103,9 +107,9 @@ __global__ __launch_bounds__(kWave *kWavesPerGroup) void waves_3p_recompute(
     MaxOf mx;
     stream<IO, kWave, U, kLoadKeep, kStoreStream>(s, mx, lane);
     const float mu = wave_max(mx.mx);
-    SumExp se{mu};
+    SumExp<IO::kIntExp> se{mu};
     stream<IO, kWave, U, kLoadKeep, kStoreStream>(s, se, lane);
-    ExpScale es(mu, 1.0f / wave_sum(se.s));
+    ExpScale<IO::kIntExp> es(mu, 1.0f / wave_sum(se.s));
     stream<IO, kWave, U, kLoadStream, kStoreStream>(s, es, lane);
 }
 
@@ -117,7 +121,7 @@ __global__ __launch_bounds__(kWave *kWavesPerGroup) void waves_3p_reload(
     MaxOf mx;
     stream<IO, kWave, U, kLoadKeep, kStoreStream>(s, mx, lane);
     const float mu = wave_max(mx.mx);
-    ExpStoreSum ess{mu};
+    ExpStoreSum<IO::kIntExp> ess{mu};
     stream<IO, kWave, U, kLoadStream, kStoreKeep>(s, ess, lane);
     const Seg<IO> sy = make_seg<IO>(y, y, n, row, 0, INT64_MAX / 2);
     Scale sc{1.0f / wave_sum(ess.s)};
@@ -220,35 +224,83 @@ __device__ __forceinline__ void feed_row(const RowRegs<IO, U> &r, uint32_t cnt, 
     }
 }
 
-// Algorithm 3 on one row held in registers: pass 1, workgroup reduction, pass 2, stores.
+// Pass 1 over the row's registers that also keeps what it computes: e[] receives every
+// element's mantissa scaled to its group's exponent, g[u] that exponent for vector slot u.
+template <class IO, int BLOCK, int U, int MODE, int U0, class P>
+__device__ __forceinline__ void feed_row_keep(const RowRegs<IO, U> &r, uint32_t cnt, P &p, float *e,
+                                              typename P::token *g)
+{
+    constexpr int V = IO::V;
+    constexpr int LEAD = lead_slots<U, MODE>();
+    constexpr int GVMAX = (U * V >= 32 ? 8 : 16) / V;
+    if constexpr (U0 < U) {
+        constexpr int GV = (U - U0) < GVMAX ? (U - U0) : GVMAX;
+        if (U0 + GV <= LEAD || threadIdx.x + (uint32_t)((U0 + GV - 1) * BLOCK) < cnt) {
+            float f[GV * V];
+#pragma unroll
+            for (int k = 0; k < GV; ++k)
+                IO::unpack(r.v[U0 + k], f + k * V);
+            p.template group<GV * V>(f, e + U0 * V);
+#pragma unroll
+            for (int k = 0; k < GV; ++k)
+                g[U0 + k] = p.exponent();
+        } else {
+#pragma unroll
+            for (int k = 0; k < GV; ++k) {
+                if (U0 + k < LEAD || threadIdx.x + (uint32_t)((U0 + k) * BLOCK) < cnt) {
+                    float f[V];
+                    IO::unpack(r.v[U0 + k], f);
+                    p.template group<V>(f, e + (U0 + k) * V);
+                }
+                g[U0 + k] = p.exponent();
+            }
+        }
+        feed_row_keep<IO, BLOCK, U, MODE, U0 + GV>(r, cnt, p, e, g);
+    }
+}
+
+// Algorithm 3 on one row held in registers.  Pass 1 leaves every element as its mantissa scaled
+// to the exponent of its group, m_i 2^(n_i - n_g): the (m, n) pairs of Section 4 with one
+// exponent shared by a group, kept in the registers that held x.  Pass 2 then needs no second
+// ExtExp: y_i = (m_i 2^(n_i - n_g)) * (lambda 2^(n_g - n_sum)), one factor per group and one
+// multiplication per element.  n_g <= n_sum, so the factor is at most lambda and nothing
+// overflows; an element more than 126 binades below its group's largest is flushed to zero,
+// and its result, below 2^-125, would be (all but) subnormal anyway.
 template <class IO, int BLOCK, int U, int MODE>
 __device__ __forceinline__ void onchip_row_2p(const Seg<IO> &s, const RowRegs<IO, U> &cur,
                                               float *lds)
 {
     constexpr int V = IO::V;
     constexpr int LEAD = lead_slots<U, MODE>();
-    PairSum acc;
-    feed_row<IO, BLOCK, U, MODE, 0>(cur, s.cnt, acc);
-    if (MODE != kTileFull && has_edge(s))
-        acc.template group<1>(&cur.edge, nullptr);
-    block_pair<BLOCK>(acc.m, acc.n, lds);
-    PairOut out(1.0f / acc.m, acc.n);
+    using Acc = PairSumOf<IO>;
+    const bool edge = MODE != kTileFull && has_edge(s);
+    Acc acc;
+    float e[U * V];
+    typename Acc::token g[U];
+    feed_row_keep<IO, BLOCK, U, MODE, 0>(cur, s.cnt, acc, e, g);
+    float e_edge = 0.f;
+    if (edge)
+        acc.template group<1>(&cur.edge, &e_edge);
+    const typename Acc::token g_edge = acc.exponent();
+    float m_sum, n_sum;
+    acc.finish(m_sum, n_sum);
+    block_pair<BLOCK>(m_sum, n_sum, lds);
+    const float lambda = 1.0f / m_sum;
     typename IO::vec *yb = s.yv + s.vb;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const uint32_t k = threadIdx.x + (uint32_t)(u * BLOCK);
         if (u < LEAD || k < s.cnt) {
-            float f[V], o[V];
-            IO::unpack(cur.v[u], f);
-            out.template group<V>(f, o);
+            const float sc = Acc::factor(lambda, g[u], n_sum);
+            float o[V];
+#pragma unroll
+            for (int i = 0; i < V; ++i)
+                o[i] = e[u * V + i] * sc;
             st<kStoreStream>(yb + k, IO::pack(o));
         }
     }
-    if (MODE != kTileFull && has_edge(s)) {
-        float o;
-        out.template group<1>(&cur.edge, &o);
-        IO::store1(s.yrow + edge_index(s), o);
-    }
+    if (edge)
+        IO::store1(s.yrow + edge_index(s), e_edge * Acc::factor(lambda, g_edge, n_sum));
 }
 
 // Algorithm 2 on one row held in registers: max, then Exp(x - mu) kept in registers where
@@ -277,12 +329,13 @@ __device__ __forceinline__ void onchip_row_3p(const Seg<IO> &s, const RowRegs<IO
         float t[V];
 #pragma unroll
         for (int i = 0; i < V; ++i)
-            t[i] = e[u * V + i] = (u < LEAD || k < s.cnt) ? exp_nonpos(f[i] - mu) : 0.f;
+            t[i] = e[u * V + i] =
+                (u < LEAD || k < s.cnt) ? exp_nonpos_as<IO::kIntExp>(f[i] - mu) : 0.f;
         part += tree_sum<V>(t);
     }
     float e_edge = 0.f;
     if (edge) {
-        e_edge = exp_nonpos(cur.edge - mu);
+        e_edge = exp_nonpos_as<IO::kIntExp>(cur.edge - mu);
         part += e_edge;
     }
     const float lambda = 1.0f / block_sum<BLOCK>(part, lds);
@@ -383,11 +436,13 @@ __global__ __launch_bounds__(BLOCK) void chunk_2p_pass1(const typename IO::elem 
     __shared__ float lds[2 * kMaxWaves];
     TP_CHUNK_PROLOGUE
     const Seg<IO> s = make_seg<IO>(x, nullptr, a.n, row, chunk, a.chunk_vecs);
-    PairSum acc;
+    PairSumOf<IO> acc;
     stream<IO, BLOCK, U, NT_FIRST, kStoreStream>(s, acc);
-    block_pair<BLOCK>(acc.m, acc.n, lds);
+    float m, n;
+    acc.finish(m, n);
+    block_pair<BLOCK>(m, n, lds);
     if (threadIdx.x == 0)
-        partial[wg] = make_float2(acc.m, acc.n);
+        partial[wg] = make_float2(m, n);
 }
 
 // Two-Pass pass 2.  pairs holds `npairs` (a few) pairs per row: the chunk partials of
@@ -401,7 +456,7 @@ __global__ __launch_bounds__(BLOCK) void chunk_2p_pass2(const typename IO::elem 
     float m_sum, n_sum;
     wave_fold_pairs(pairs + row * npairs, npairs, m_sum, n_sum);
     const Seg<IO> s = make_seg<IO>(x, y, a.n, row, chunk, a.chunk_vecs);
-    PairOut out(1.0f / m_sum, n_sum);
+    PairOutOf<IO> out(1.0f / m_sum, n_sum);
     stream<IO, BLOCK, U, kLoadStream, kStoreStream>(s, out);
 }
 
@@ -426,7 +481,7 @@ __global__ __launch_bounds__(BLOCK) void chunk_sumexp(const typename IO::elem *x
     __shared__ float lds[2 * kMaxWaves];
     TP_CHUNK_PROLOGUE
     const Seg<IO> s = make_seg<IO>(x, nullptr, a.n, row, chunk, a.chunk_vecs);
-    SumExp se{wave_fold_max(maxes + row * nmax, nmax)};
+    SumExp<IO::kIntExp> se{wave_fold_max(maxes + row * nmax, nmax)};
     stream<IO, BLOCK, U, NT_FIRST, kStoreStream>(s, se);
     const float v = block_sum<BLOCK>(se.s, lds);
     if (threadIdx.x == 0)
@@ -443,7 +498,7 @@ __global__ __launch_bounds__(BLOCK) void chunk_expscale(const typename IO::elem 
     const float mu = wave_fold_max(maxes + row * nmax, nmax);
     const float sigma = wave_fold_sum(sums + row * nsum, nsum);
     const Seg<IO> s = make_seg<IO>(x, y, a.n, row, chunk, a.chunk_vecs);
-    ExpScale es(mu, 1.0f / sigma);
+    ExpScale<IO::kIntExp> es(mu, 1.0f / sigma);
     stream<IO, BLOCK, U, kLoadStream, kStoreStream>(s, es);
 }
 
@@ -455,7 +510,7 @@ __global__ __launch_bounds__(BLOCK) void chunk_expstore(const typename IO::elem 
     __shared__ float lds[2 * kMaxWaves];
     TP_CHUNK_PROLOGUE
     const Seg<IO> s = make_seg<IO>(x, y, a.n, row, chunk, a.chunk_vecs);
-    ExpStoreSum ess{wave_fold_max(maxes + row * nmax, nmax)};
+    ExpStoreSum<IO::kIntExp> ess{wave_fold_max(maxes + row * nmax, nmax)};
     stream<IO, BLOCK, U, kLoadStream, kStoreKeep>(s, ess);
     const float v = block_sum<BLOCK>(ess.s, lds);
     if (threadIdx.x == 0)

@@ -170,13 +170,15 @@ def test_tuning_keys(B):
     assert B.softmax_tp_plan(1, 1 << 28).map.block == 128
 
 
-def test_constants_header_is_what_the_generator_writes():
+def test_constants_header_is_what_the_generator_writes(tmp_path):
     csrc = os.path.join(ROOT, "paper_2001_04438_amd", "csrc")
     committed = open(os.path.join(csrc, "expconst.h")).read()
-    out = subprocess.run([sys.executable, os.path.join(csrc, "gen_expconst.py")], check=True,
-                         capture_output=True, text=True).stdout
+    out_path = tmp_path / "expconst.h"
+    out = subprocess.run([sys.executable, os.path.join(csrc, "gen_expconst.py"), str(out_path)],
+                         check=True, capture_output=True, text=True).stdout
     assert out.strip() == committed.strip()
-    assert open(os.path.join(csrc, "expconst.h")).read() == committed
+    assert out_path.read_text().strip() == committed.strip()
+    assert open(os.path.join(csrc, "expconst.h")).read() == committed     # the tracked file is not touched
 
 
 def test_fp32_extexp_accuracy_on_the_host(tmp_path):
@@ -201,6 +203,28 @@ def test_fp32_extexp_accuracy_on_the_host(tmp_path):
     out = subprocess.run([str(exe), "-100000", "100000", "4001", threads], check=True,
                          capture_output=True, text=True).stdout.split()
     assert int(out[4]) == 0 and 0.70 < float(out[2]) and float(out[3]) < 1.43
+
+
+def test_integer_exponent_evaluator_on_the_host(tmp_path):
+    """The evaluator of the 16-bit storage formats (exponent read from the bit pattern of the
+    rounded sum, one-constant reduction), swept the same way: n from the bits equals
+    z - 1.5 * 2^23 and round(x log2 e) everywhere up to |x| = 2.9e6; against what it approximates by
+    design, e^(x - n fl(ln 2)) 2^n, it is as accurate as Algorithm 4 (< 2 ULP); against e^x itself
+    the one-constant reduction costs |n| * 1.9e-9, i.e. < 5.5 ULP where fp32 exp is finite."""
+    exe = tmp_path / "sweep"
+    subprocess.run(["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-mfma", "-o", str(exe),
+                    os.path.join(ROOT, "tests", "host_extexp_sweep.c"), "-lm", "-lpthread"], check=True)
+    threads = str(min(16, os.cpu_count() or 1))
+    out = subprocess.run([str(exe), "-104", "89", "9", threads, "2", "1"], check=True,
+                         capture_output=True, text=True).stdout.split()
+    assert int(out[0]) > 2.2e9 / 9 * 0.99
+    assert float(out[1]) < 2.0 and int(out[4]) == 0, out
+    assert 2.0 < float(out[6]) < 5.5, out           # the dropped term is visible, and bounded
+    assert math.sqrt(2) / 2 * (1 - 1e-5) <= float(out[2]) and float(out[3]) <= math.sqrt(2) * (1 + 1e-5)
+    for lo, hi, stride in (("-100000", "100000", "4001"), ("-2900000", "2900000", "40001")):
+        out = subprocess.run([str(exe), lo, hi, stride, threads, "0", "1"], check=True,
+                             capture_output=True, text=True).stdout.split()
+        assert int(out[4]) == 0 and 0.69 < float(out[2]) and float(out[3]) < 1.45, out
 
 
 def test_header_is_plain_c_and_cxx(tmp_path):
