@@ -203,6 +203,43 @@ def run_workload(torch, B, W, name, steps, warmup, full):
     return out, x_host, y_host
 
 
+def calls_only(torch, B, W, name, variants, steps, warmup):
+    """Profiler target: nothing but the named calls on the named workload (one buffer set)."""
+    import numpy as np
+    base, f16 = (name[:-4], True) if name.endswith("_f16") else (name, False)
+    rows, n = W.SHAPES[base]
+    x_host = W.make(base)
+    if f16:
+        vals = W.bf16_bits_to_f32(x_host) if W.DTYPES[base] == "bf16" else x_host
+        x_host = W.f32_to_f16_bits(vals).reshape(rows, n)
+    fmt = "f16" if f16 else W.DTYPES[base]
+    flat = x_host.reshape(-1)
+    x = torch.from_numpy(flat.view(np.int16) if fmt != "f32" else flat).cuda()
+    y = torch.empty_like(x)
+    suffix = {"f32": "_f32", "bf16": "_bf16io", "f16": "_f16io"}[fmt]
+    out = {}
+    for v in variants:
+        if v == "copy":
+            if fmt == "f32":
+                fn = lambda: B.softmax_tp_stream_copy_f32(x, y, rows * n)
+            else:   # the same bytes as fp32 words
+                fn = lambda: B.softmax_tp_stream_copy_f32(x.data_ptr(), y.data_ptr(), rows * n // 2)
+        else:
+            fn = lambda f=getattr(B, v + suffix): f(x, y, rows, n)
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        out[v] = (time.perf_counter() - t0) * 1e3 / steps
+        log(f"[bench] {name} {v}: {out[v]:.4f} ms per call ({steps} calls)")
+    B.softmax_tp_release()
+    print(json.dumps({"workload": name, "rows": rows, "n": n, "dtype": fmt, "calls": steps,
+                      "warmup": warmup, "ms_per_call": out}))
+
+
 def calibration(torch, B, steps, warmup):
     n = 1 << 28
     x = torch.rand(n, dtype=torch.float32, device="cuda")
@@ -259,8 +296,12 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg4", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg4", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg5_f16"])
     ap.add_argument("--quick", action="store_true", help="headline workload only")
+    ap.add_argument("--calls-only", default="", metavar="VARIANT[,VARIANT...]",
+                    help="for profiler runs: generate the workload, make --warmup + --steps calls of each "
+                         "named variant (softmax2p, softmax3p_recompute, softmax3p_reload, softmax2p_onchip, "
+                         "softmax3p_onchip, copy) and exit; no oracle, no other workload")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -275,6 +316,10 @@ def main():
     torch.cuda.set_device(0)
     props = torch.cuda.get_device_properties(0)
     log(f"[bench] device: {props.name}, {props.multi_processor_count} CUs")
+
+    if args.calls_only:
+        calls_only(torch, B, W, args.workload, args.calls_only.split(","), args.steps, args.warmup)
+        return
 
     head, x_host, y_host = run_workload(torch, B, W, args.workload, args.steps, args.warmup, True)
     bf16 = head["dtype"] == "bf16"

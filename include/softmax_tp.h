@@ -115,10 +115,12 @@ TP_API int softmax3p_reload_f16io(const uint16_t *x, uint16_t *y, int64_t rows, 
 
 /*
  * On-chip variant of Algorithm 3 for short rows (n <= TP_ONCHIP_MAX_N): a workgroup
- * loads a row into registers, runs pass 1 and pass 2 on the registers and writes y, while
- * the loads of its next row are already in flight.  Same arithmetic and results as
- * softmax2p_f32 / _bf16io / _f16io up to summation order, but x is read from memory only
- * once (2 N elements of traffic instead of 3 N): the regime in which, as the paper notes
+ * loads its row into registers, runs pass 1 on them, keeps every element as its mantissa
+ * scaled to a group exponent (the (m, n) pairs of Section 4 with one n per group of 8 or 16
+ * elements), and pass 2 multiplies by lambda * 2^(n_group - n_sum) and writes y.  Same
+ * results as softmax2p_f32 / _bf16io / _f16io up to rounding order, but x is read from memory
+ * only once (2 N elements of traffic instead of 3 N) and ExtExp is evaluated once per element:
+ * the regime in which, as the paper notes
  * (Sections 6.4 and 7), the Two-Pass algorithm has no bandwidth advantage left to offer.
  * Kept as an entry point of its own so that its throughput is never mistaken for the
  * three-traversal algorithm's.  x and y must be congruent modulo 16 bytes

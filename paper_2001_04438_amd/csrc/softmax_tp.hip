@@ -548,44 +548,13 @@ static bool onchip_shape(int64_t lo, int64_t hi, bool exact, int unroll_max, Onc
     return true;
 }
 
-// Workgroups of `kernel` that fit on the device at once (cached per device and kernel).
-static int resident_workgroups(const void *kernel, int block, int *out)
-{
-    static std::mutex mu;
-    static std::map<std::pair<int, const void *>, int> cache;
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess)
-        return (int)e;
-    std::lock_guard<std::mutex> lock(mu);
-    auto it = cache.find(std::make_pair(dev, kernel));
-    if (it == cache.end()) {
-        int per_cu = 0, cus = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, block, 0);
-        if (e != hipSuccess)
-            return (int)e;
-        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e != hipSuccess)
-            return (int)e;
-        if (per_cu < 1) per_cu = 1;
-        it = cache.emplace(std::make_pair(dev, kernel), per_cu * cus).first;
-    }
-    *out = it->second;
-    return TP_OK;
-}
-
 template <class IO, int B, int U, int MODE>
 static int launch_onchip(int algo, const typename IO::elem *x, typename IO::elem *y, int64_t rows,
                          int64_t n, hipStream_t st)
 {
     auto kernel = algo == kOnchipTwoPass ? rows_onchip<IO, B, U, MODE, kOnchipTwoPass>
                                          : rows_onchip<IO, B, U, MODE, kOnchipThreePass>;
-    int resident = 0;
-    int rc = resident_workgroups((const void *)kernel, B, &resident);
-    if (rc != TP_OK)
-        return rc;
-    const int64_t grid = rows < resident ? rows : resident;
-    return launch(kernel, dim3((uint32_t)grid), dim3(B), st, x, y, n, rows);
+    return launch(kernel, dim3((uint32_t)rows), dim3(B), st, x, y, n);
 }
 
 template <class IO, int B, int U>
@@ -622,7 +591,7 @@ static int run_onchip(int algo, const typename IO::elem *x, typename IO::elem *y
     const int64_t hi = (n + V - 1) / V;
     const int64_t lo = exact ? n / V : (n / V > 0 ? n / V - 1 : 0);
     OnchipShape sh;
-    if (!onchip_shape(lo, hi, exact, umax, &sh))
+    if (!onchip_shape(lo, hi, exact, umax, &sh) || rows > kGridMax || rows > kThreadsMax / 1024)
         return TP_ERR_TOO_LARGE;
     hipStream_t st = (hipStream_t)stream;
 #define TP_OC(B, UU)                                                              \
