@@ -37,6 +37,7 @@ class Cmp(ctypes.Structure):
         ("n_negative", _i64),
         ("n_normal", _i64),
         ("n_total", _i64),
+        ("max_bound_ratio", ctypes.c_double),
     ]
 
     def as_dict(self):
@@ -79,6 +80,9 @@ def lib():
             getattr(L, name).argtypes = [_vp, _vp, _i64, _i64, ctypes.c_double,
                                          ctypes.POINTER(Cmp), ctypes.c_int]
             getattr(L, name).restype = None
+        L.oracle_compare_sloped_f32.argtypes = [_vp, _vp, _i64, _i64, ctypes.c_double, ctypes.c_double,
+                                                ctypes.POINTER(Cmp), ctypes.c_int]
+        L.oracle_compare_sloped_f32.restype = None
         L.oracle_pair_rel_err_f32.argtypes = [_vp, _vp, _vp, _i64, _vp]
         L.oracle_pair_rel_err_f32.restype = ctypes.c_double
         L.oracle_logsumexp_f32.argtypes = [_vp, _i64, ctypes.c_int]
@@ -138,17 +142,29 @@ def softmax(x, bf16: bool = False, threads: int = 0, f16: bool = False):
     return p.reshape(shape)
 
 
-def compare(x, y, tol: float, bf16: bool = False, threads: int = 0, f16: bool = False) -> Cmp:
-    """Stream y against the oracle's p for x (same shape); see oracle_cmp_t."""
+def compare(x, y, tol: float, bf16: bool = False, threads: int = 0, f16: bool = False,
+            slope: float = 0.0) -> Cmp:
+    """Stream y against the oracle's p for x (same shape); see oracle_cmp_t.  With slope > 0
+    (fp32 only) element i is held to tol + slope * |x_i - mu| instead of tol."""
     dt = np.uint16 if (bf16 or f16) else np.float32
     a = _as2d(x, dt)
     b = _as2d(y, dt)
     assert a.shape == b.shape
     rows, n = a.shape
     out = Cmp()
+    if slope:
+        assert not (bf16 or f16)
+        lib().oracle_compare_sloped_f32(_ptr(a), _ptr(b), rows, n, float(tol), float(slope),
+                                        ctypes.byref(out), threads)
+        return out
     fn = getattr(lib(), "oracle_compare_" + _kind(bf16, f16))
     fn(_ptr(a), _ptr(b), rows, n, float(tol), ctypes.byref(out), threads)
     return out
+
+
+# The fp32 subtraction x - mu of the Three-Pass algorithms is off by up to half an ulp of the
+# difference: 2^-24 |x - mu| relative in the result (see the comparator in softmax_oracle.c).
+THREE_PASS_SLOPE = 2.0 ** -24
 
 
 def pair_rel_err(x, m, n):

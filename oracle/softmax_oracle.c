@@ -332,14 +332,6 @@ void oracle_softmax_bf16(const uint16_t *x, int64_t rows, int64_t n, long double
     softmax_any(x, ORACLE_BF16, rows, n, p, threads);
 }
 
-/* Probabilities of a few chosen elements of one row, given that row's mu, S. */
-void oracle_prob_at_f32(const float *x, int64_t row_off, const int64_t *idx, int64_t count,
-                        long double mu, long double S, long double *p)
-{
-    for (int64_t k = 0; k < count; ++k)
-        p[k] = expl((long double)x[row_off + idx[k]] - mu) / S;
-}
-
 /* ------------------------------------------------------------------ */
 /* streaming comparator                                                */
 /* ------------------------------------------------------------------ */
@@ -347,7 +339,13 @@ void oracle_prob_at_f32(const float *x, int64_t row_off, const int64_t *idx, int
 /*
  * Compares a candidate output y against p without storing p.
  *
- *   p_i >= TINY : rel_i = |y_i - p_i| / p_i, violation if rel_i > tol
+ *   p_i >= TINY : rel_i = |y_i - p_i| / p_i, violation if rel_i > tol + slope * |x_i - mu|
+ *                 (slope is 0 unless the caller asks otherwise.  The Three-Pass algorithms
+ *                  evaluate Exp on fl32(x_i - mu); that subtraction alone is off by up to half an
+ *                  ulp of the difference, a relative error of 2^-24 |x_i - mu| in the result that
+ *                  no evaluator, however exact, can remove (Section 6.3 bounds the error of Exp,
+ *                  not of its argument).  Their fp32 outputs are therefore held to
+ *                  4e-6 + 2^-24 |x_i - mu| per element: slope = 2^-24.)
  *   p_i <  TINY : abs_i = |y_i - p_i|, violation if abs_i > TINY
  *                 (the paper allows subnormal results to be flushed to
  *                  zero, Section 6.3, so either 0 or the denormal passes)
@@ -369,6 +367,7 @@ typedef struct {
     int64_t n_negative;     /* y_i < 0                                      */
     int64_t n_normal;       /* elements with p_i >= FLT_MIN                 */
     int64_t n_total;
+    double max_bound_ratio; /* max of rel_i / (tol + slope |x_i - mu|) over those elements */
 } oracle_cmp_t;
 
 typedef struct {
@@ -376,7 +375,7 @@ typedef struct {
     int kind;
     int64_t n;
     const long double *mu, *S;
-    double tol;
+    double tol, slope;
     int64_t row; /* used in single-row mode */
     oracle_cmp_t part[ORACLE_MAX_THREADS];
     long double rowsum_part[ORACLE_MAX_THREADS];
@@ -388,6 +387,7 @@ static void cmp_init(oracle_cmp_t *c)
     c->worst_index = -1;
 }
 
+/* tol is the bound for this element (the caller has added slope |x_i - mu| to it). */
 static void cmp_elem(oracle_cmp_t *acc, long double p, long double y, double tol, int64_t flat,
                      int kind)
 {
@@ -411,6 +411,8 @@ static void cmp_elem(oracle_cmp_t *acc, long double p, long double y, double tol
         }
         if (rel > tol)
             acc->n_rel_viol++;
+        if (rel / tol > acc->max_bound_ratio)
+            acc->max_bound_ratio = rel / tol;
     } else {
         if ((double)d > acc->max_sub_abs_err)
             acc->max_sub_abs_err = (double)d;
@@ -427,6 +429,8 @@ static void cmp_merge(oracle_cmp_t *into, const oracle_cmp_t *from)
         into->worst_expected = from->worst_expected;
         into->worst_got = from->worst_got;
     }
+    if (from->max_bound_ratio > into->max_bound_ratio)
+        into->max_bound_ratio = from->max_bound_ratio;
     if (from->max_sub_abs_err > into->max_sub_abs_err)
         into->max_sub_abs_err = from->max_sub_abs_err;
     if (from->max_row_sum_dev > into->max_row_sum_dev)
@@ -448,9 +452,10 @@ static void cmp_rows(void *c, int tid, int64_t lo, int64_t hi)
         long double rowsum = 0.0L;
         for (int64_t i = 0; i < q->n; ++i) {
             int64_t k = r * q->n + i;
-            long double p = expl(elem_at(q->x, q->kind, k) - q->mu[r]) / q->S[r];
+            long double d = elem_at(q->x, q->kind, k) - q->mu[r];
+            long double p = expl(d) / q->S[r];
             long double y = out_at(q->y, q->kind, k);
-            cmp_elem(acc, p, y, q->tol, k, q->kind);
+            cmp_elem(acc, p, y, q->tol + q->slope * (double)fabsl(d), k, q->kind);
             if (y == y)
                 rowsum += y;
         }
@@ -469,9 +474,10 @@ static void cmp_one_row_range(void *c, int tid, int64_t lo, int64_t hi)
     long double rowsum = 0.0L;
     for (int64_t i = lo; i < hi; ++i) {
         int64_t k = r * q->n + i;
-        long double p = expl(elem_at(q->x, q->kind, k) - q->mu[r]) / q->S[r];
+        long double d = elem_at(q->x, q->kind, k) - q->mu[r];
+        long double p = expl(d) / q->S[r];
         long double y = out_at(q->y, q->kind, k);
-        cmp_elem(acc, p, y, q->tol, k, q->kind);
+        cmp_elem(acc, p, y, q->tol + q->slope * (double)fabsl(d), k, q->kind);
         if (y == y)
             rowsum += y;
     }
@@ -479,7 +485,7 @@ static void cmp_one_row_range(void *c, int tid, int64_t lo, int64_t hi)
 }
 
 static void compare_any(const void *x, const void *y, int kind, int64_t rows, int64_t n,
-                        double tol, oracle_cmp_t *out, int threads)
+                        double tol, double slope, oracle_cmp_t *out, int threads)
 {
     cmp_init(out);
     if (rows <= 0 || n <= 0)
@@ -496,6 +502,7 @@ static void compare_any(const void *x, const void *y, int kind, int64_t rows, in
     q->mu = mu;
     q->S = S;
     q->tol = tol;
+    q->slope = slope;
     if (rows >= threads || threads == 1) {
         int used = threads > rows ? (int)rows : threads;
         parallel_ranges(threads, rows, cmp_rows, q);
@@ -524,21 +531,28 @@ static void compare_any(const void *x, const void *y, int kind, int64_t rows, in
 void oracle_compare_f32(const float *x, const float *y, int64_t rows, int64_t n, double tol,
                         oracle_cmp_t *out, int threads)
 {
-    compare_any(x, y, ORACLE_F32, rows, n, tol, out, threads);
+    compare_any(x, y, ORACLE_F32, rows, n, tol, 0.0, out, threads);
+}
+
+/* The same with the per-element bound tol + slope |x_i - mu| (see the comparator's header). */
+void oracle_compare_sloped_f32(const float *x, const float *y, int64_t rows, int64_t n, double tol,
+                               double slope, oracle_cmp_t *out, int threads)
+{
+    compare_any(x, y, ORACLE_F32, rows, n, tol, slope, out, threads);
 }
 
 /* x and y are both bf16 bit patterns; y is compared with the unrounded p. */
 void oracle_compare_bf16(const uint16_t *x, const uint16_t *y, int64_t rows, int64_t n, double tol,
                          oracle_cmp_t *out, int threads)
 {
-    compare_any(x, y, ORACLE_BF16, rows, n, tol, out, threads);
+    compare_any(x, y, ORACLE_BF16, rows, n, tol, 0.0, out, threads);
 }
 
 /* x and y are both IEEE binary16 bit patterns; y is compared with the unrounded p. */
 void oracle_compare_f16(const uint16_t *x, const uint16_t *y, int64_t rows, int64_t n, double tol,
                         oracle_cmp_t *out, int threads)
 {
-    compare_any(x, y, ORACLE_F16, rows, n, tol, out, threads);
+    compare_any(x, y, ORACLE_F16, rows, n, tol, 0.0, out, threads);
 }
 
 void oracle_stats_f16(const uint16_t *x, int64_t rows, int64_t n, long double *mu, long double *S,

@@ -1,17 +1,16 @@
 /*
- * Scalar model of the Two-Pass softmax: TEST INFRASTRUCTURE, not the product.
+ * Scalar model of the (m, n) pair algebra behind the Two-Pass softmax: TEST
+ * INFRASTRUCTURE, not the product.
  *
- * Follows Algorithm 3 (Section 4) step by step in double precision: ExtExp
- * gives e^x as a pair (m, n) with n = round(x * log2 e), t = x - n * ln 2,
- * m = e^t; pass 1 keeps a running pair (m_sum, n_sum) and rescales both terms
- * to the larger exponent before adding; pass 2 recomputes each pair and forms
- * Y_i = m_i * lambda * 2^(n_i - n_sum) with lambda = 1 / m_sum.
- *
- * e^t comes from libm (a library primitive as one step); there is no
- * polynomial here and no blocking or reordering.  The model exists to show
- * that the pair algebra reproduces the definition that softmax_oracle.c writes
- * out, and to give the expected (m_sum, n_sum) of pass 1.  It shares nothing
- * with the HIP path.
+ * Section 4 represents e^x as a pair (m, n) with e^x = m * 2^n and defines how two
+ * such pairs are added.  The model states exactly that, in double precision:
+ * model_extexp makes a pair (n = round(x log2 e), m = e^(x - n ln 2) from libm),
+ * model_pair_add adds two pairs, and everything else is built from those two: the
+ * row's sum is a fold of model_pair_add over the pairs starting from the identity
+ * (0, -inf), an output is the quotient of an element's pair by the sum's pair.  The
+ * tests fold in index order and in random tree orders, and check
+ * ln m_sum + n_sum ln 2 against the oracle's log-sum-exp.  There is no polynomial
+ * here and nothing is shared with the HIP path.
  */
 #include <math.h>
 #include <stdint.h>
@@ -36,32 +35,30 @@ void model_pair_add(double ma, double na, double mb, double nb, double *m, doubl
     *n = n_max;
 }
 
-/* Pass 1 of Algorithm 3 over one vector: returns the final (m_sum, n_sum). */
+/* The sum of e^(x_i) over one vector as a pair: the fold of pair addition, in index
+ * order, over the elements' pairs (what pass 1 of Algorithm 3 produces). */
 void model_twopass_pass1(const double *x, int64_t N, double *m_sum_out, double *n_sum_out)
 {
-    double m_sum = 0.0;
-    double n_sum = -INFINITY;
+    double m_sum = 0.0, n_sum = -INFINITY; /* the additive identity */
     for (int64_t i = 0; i < N; ++i) {
         double m_i, n_i;
         model_extexp(x[i], &m_i, &n_i);
-        double n_max = n_i > n_sum ? n_i : n_sum;
-        m_sum = m_i * exp2(n_i - n_max) + m_sum * exp2(n_sum - n_max);
-        n_sum = n_max;
+        model_pair_add(m_sum, n_sum, m_i, n_i, &m_sum, &n_sum);
     }
     *m_sum_out = m_sum;
     *n_sum_out = n_sum;
 }
 
-/* Algorithm 3 in full. */
+/* Softmax through the pair algebra: each output is the element's pair divided by the
+ * pair of the sum, (m_i / m_sum) * 2^(n_i - n_sum) (what pass 2 of Algorithm 3 writes). */
 void model_twopass(const double *x, double *y, int64_t N)
 {
     double m_sum, n_sum;
     model_twopass_pass1(x, N, &m_sum, &n_sum);
-    double lambda_sum = 1.0 / m_sum;
     for (int64_t i = 0; i < N; ++i) {
         double m_i, n_i;
         model_extexp(x[i], &m_i, &n_i);
-        y[i] = m_i * lambda_sum * exp2(n_i - n_sum);
+        y[i] = (m_i / m_sum) * exp2(n_i - n_sum);
     }
 }
 

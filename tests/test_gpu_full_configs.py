@@ -35,7 +35,10 @@ def _run(fn, x):
     return (y.view(np.uint16) if flat.dtype == np.uint16 else y).reshape(rows, n)
 
 
-F32 = [("softmax2p_f32", 4e-6), ("softmax3p_recompute_f32", 1e-5), ("softmax3p_reload_f32", 1e-5)]
+# (entry point, tolerance, allowance per unit of |x_i - mu|): the Three-Pass algorithms round
+# x - mu to fp32 before Exp sees it, which costs up to 2^-24 |x_i - mu| relative per element
+F32 = [("softmax2p_f32", 4e-6, 0.0), ("softmax3p_recompute_f32", 4e-6, 2.0 ** -24),
+       ("softmax3p_reload_f32", 4e-6, 2.0 ** -24)]
 
 
 @pytest.mark.parametrize("cfg", ["cfg2", "cfg3", "cfg4"])
@@ -43,12 +46,13 @@ def test_full_size_fp32(gpu, oracle_mod, cfg):
     x = workloads.make(cfg)
     rows, n = x.shape
     print(f"{cfg}: {rows} x {n}", flush=True)
-    for name, tol in F32:
+    for name, tol, slope in F32:
         y = _run(getattr(gpu, name), x)
-        c = oracle_mod.compare(x, y, tol)
-        print(f"  {name}: max_rel_err={c.max_rel_err:.3e} row_sum_dev={c.max_row_sum_dev:.3e}", flush=True)
+        c = oracle_mod.compare(x, y, tol, slope=slope)
+        print(f"  {name}: max_rel_err={c.max_rel_err:.3e} of-bound={c.max_bound_ratio:.3f} "
+              f"row_sum_dev={c.max_row_sum_dev:.3e}", flush=True)
         assert c.n_total == x.size and c.ok(), (name, c.as_dict())
-        assert c.max_row_sum_dev <= tol + n * 2.0 ** -126
+        assert c.max_row_sum_dev <= (1e-5 if slope else tol) + n * 2.0 ** -126
 
 
 def test_full_size_cfg4_structure(gpu):

@@ -5,8 +5,9 @@ compare element by element with the oracle's streaming comparator:
 
   fp32 I/O, Two-Pass     |y - p| <= 4e-6 p      where p >= FLT_MIN
   bf16 I/O, Two-Pass     |y - p| <= 1e-2 p      (p is the unrounded long-double value)
-  fp32 I/O, Three-Pass   |y - p| <= 1e-5 p      (the fp32 subtraction x - mu alone costs up to
-                                                 2^-24 |x - mu| <= 5.2e-6 while p >= FLT_MIN)
+  fp32 I/O, Three-Pass   |y - p| <= (4e-6 + 2^-24 |x - mu|) p, element by element: the fp32
+                                                 subtraction x - mu alone costs up to 2^-24 |x - mu|
+                                                 (<= 5.2e-6 while p >= FLT_MIN) before Exp is even called
   fp16 I/O               |y - p| <= 5e-4 p      where p >= 2^-14: one rounding to 11 bits (2^-11 =
                                                  4.883e-4) on top of the fp32 result; 1.1e-3 for
                                                  the reloading variant, which rounds twice
@@ -24,8 +25,18 @@ from paper_2001_04438_amd import workloads
 
 pytestmark = pytest.mark.gpu
 
+class Bound(float):
+    """A relative tolerance that may grow with |x_i - mu| (slope > 0: the Three-Pass rule)."""
+    slope = 0.0
+
+    def __new__(cls, tol, slope=0.0):
+        b = super().__new__(cls, tol)
+        b.slope = slope
+        return b
+
+
 TOL_2P = 4e-6
-TOL_3P = 1e-5
+TOL_3P = Bound(4e-6, slope=2.0 ** -24)
 TOL_BF16 = 1e-2
 TOL_F16 = 5e-4
 TOL_F16_RELOAD = 1.1e-3
@@ -71,12 +82,15 @@ def _run(fn, x, inplace=False, x_off=0, y_off=0):
 
 
 def _check(oracle_mod, x, y, tol, bf16=False, f16=False):
-    c = oracle_mod.compare(x, y, tol, bf16=bf16, f16=f16)
+    slope = getattr(tol, "slope", 0.0)
+    c = oracle_mod.compare(x, y, float(tol), bf16=bf16, f16=f16, slope=slope)
     n = x.shape[1]
     assert c.n_total == x.size
     assert c.ok(), c.as_dict()
     if f16:
         assert c.max_row_sum_dev <= 2 * tol + n * 2.0 ** -25, c.as_dict()
+    elif slope:   # the allowance weighs in with sum_i p_i |x_i - mu| 2^-24, and p e^-|d| |d| <= 1 / e
+        assert c.max_row_sum_dev <= 1e-5 + n * 2.0 ** -126, c.as_dict()
     else:
         assert c.max_row_sum_dev <= (tol if not bf16 else 2 * tol) + n * 2.0 ** -126, c.as_dict()
     return c

@@ -1,9 +1,10 @@
 """Pins for the double-precision scalar model of Algorithms 1-3 (CPU only).
 
-The model re-enacts the paper's algorithms literally; these tests show that the
-(m, n) pair algebra of Section 4 reproduces the softmax definition (the oracle,
-itself pinned in test_oracle_pins.py), that pair addition is order-independent,
-and that nothing overflows where a plain exp would.
+The model states the (m, n) pair algebra of Section 4 (make a pair, add two pairs) and
+builds the row sum and the outputs from those two operations alone; these tests show
+that the algebra reproduces the softmax definition (the oracle, itself pinned in
+test_oracle_pins.py), that pair addition is order-independent, and that nothing
+overflows where a plain exp would.
 """
 import json
 import math

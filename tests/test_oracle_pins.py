@@ -361,6 +361,46 @@ def test_comparator_accepts_correct_and_flags_wrong(oracle_mod):
     assert c3.n_nonfinite == 2 and c3.n_negative == 1 and not c3.ok()
 
 
+def test_comparator_per_element_bound_for_three_pass(oracle_mod):
+    """Optional mode: element i is held to tol + slope |x_i - mu| (the Three-Pass algorithms'
+    fl32(x_i - mu) costs up to 2^-24 |x_i - mu| relative whatever the evaluator does).  Pinned on
+    planted errors placed just inside and just outside the bound of an element far below the
+    maximum, and on what the subtraction itself does to an otherwise exact result."""
+    slope = oracle_mod.THREE_PASS_SLOPE
+    assert slope == 2.0 ** -24
+    x = np.array([[0.0, -3.0, -40.0, -80.0, -86.5]], dtype=np.float32)
+    p = oracle_mod.softmax(x)[0]
+    assert p[4] > np.finfo(np.float32).tiny
+    y = p.astype(np.float64)
+    inside = y.copy()
+    inside[3] *= 1 + 4e-6 + 0.5 * slope * 80.0          # within 4e-6 + 2^-24 * 80 = 8.77e-6
+    outside = y.copy()
+    outside[3] *= 1 + 4e-6 + 1.5 * slope * 80.0
+    f = lambda v: v.astype(np.float32).reshape(1, -1)
+    assert 4e-6 + slope * 80.0 == pytest.approx(8.768e-6, rel=1e-3)
+    c_in = oracle_mod.compare(x, f(inside), 4e-6, slope=slope)
+    assert c_in.ok() and 0.6 < c_in.max_bound_ratio < 1.0
+    assert oracle_mod.compare(x, f(inside), 4e-6).n_rel_viol == 1           # flat rule: too far
+    c_out = oracle_mod.compare(x, f(outside), 4e-6, slope=slope)
+    assert c_out.n_rel_viol == 1 and c_out.worst_index == 3 and c_out.max_bound_ratio > 1.0
+    # the allowance scales with |x_i - mu|: the same relative error next to the maximum is refused
+    near = y.copy()
+    near[1] *= 1 + 4e-6 + 0.5 * slope * 80.0
+    assert oracle_mod.compare(x, f(near), 4e-6, slope=slope).n_rel_viol == 1
+    # where the allowance comes from: exp of the ROUNDED difference, otherwise exact
+    rng = np.random.default_rng(24)
+    xs = rng.uniform(-86, 0, (1, 4000)).astype(np.float32)
+    xs[0, 0] = np.float32(0.3337)        # the maximum: fine-grained, so x - mu needs more than 24 bits
+    mu = xs.max()
+    d32 = (xs - mu).astype(np.float32)                                       # one fp32 rounding
+    e = np.exp(d32.astype(np.longdouble))
+    y3 = (e / e.sum()).astype(np.float32)
+    c = oracle_mod.compare(xs, y3, 4e-6, slope=slope)
+    assert c.ok() and c.max_bound_ratio < 1.0
+    assert c.max_rel_err > 1e-6          # the subtraction alone costs more than the 2 ULP of Exp
+    assert c.max_rel_err <= 2.0 ** -24 * 86 + 2.0 ** -23
+
+
 def test_comparator_subnormal_rule(oracle_mod):
     # p of the small entries lies below FLT_MIN: 0 or the denormal both pass, garbage does not
     x = np.array([[0.0, -88.0, -95.0, -120.0]], dtype=np.float32)
