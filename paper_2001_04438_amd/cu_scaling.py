@@ -11,9 +11,62 @@ cache for every thread count.  Prints a markdown table.
 from __future__ import annotations
 
 import argparse
+import contextlib
 import ctypes
 import sys
 import time
+
+_hip = None
+
+
+def hip():
+    """The HIP runtime, for the three stream calls torch has no binding for."""
+    global _hip
+    if _hip is None:
+        h = ctypes.CDLL("libamdhip64.so")
+        h.hipExtStreamCreateWithCUMask.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint32,
+                                                   ctypes.POINTER(ctypes.c_uint32)]
+        h.hipStreamSynchronize.argtypes = [ctypes.c_void_p]
+        h.hipStreamDestroy.argtypes = [ctypes.c_void_p]
+        _hip = h
+    return _hip
+
+
+@contextlib.contextmanager
+def masked_stream(k, cus):
+    """A HIP stream (default priority) whose kernels run on the first k of the device's `cus`
+    compute units only; yields the raw hipStream_t value.  Synchronised and destroyed on exit."""
+    if not 1 <= k <= cus:
+        raise ValueError(f"k = {k} outside 1..{cus}")
+    words = (cus + 31) // 32
+    mask = (ctypes.c_uint32 * words)()
+    for i in range(k):
+        mask[i // 32] |= 1 << (i % 32)
+    st = ctypes.c_void_p()
+    rc = hip().hipExtStreamCreateWithCUMask(ctypes.byref(st), words, mask)
+    if rc != 0:
+        raise RuntimeError(f"hipExtStreamCreateWithCUMask failed with {rc}")
+    try:
+        yield st.value
+    finally:
+        hip().hipStreamSynchronize(st)
+        hip().hipStreamDestroy(st)
+
+
+def time_on_stream(fn, stream, iters):
+    """Host-clock milliseconds per call of fn(stream) over `iters` calls, after at least 50 ms and
+    two untimed calls."""
+    w0 = time.perf_counter()
+    warm = 0
+    while warm < 2 or time.perf_counter() - w0 < 0.05:
+        fn(stream)
+        hip().hipStreamSynchronize(stream)
+        warm += 1
+    t0 = time.perf_counter()
+    for _ in range(iters):
+        fn(stream)
+    hip().hipStreamSynchronize(stream)
+    return (time.perf_counter() - t0) / iters * 1e3
 
 
 def main():
@@ -25,43 +78,19 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("needs a GPU")
     B.lib()
-    hip = ctypes.CDLL("libamdhip64.so")
-    hip.hipExtStreamCreateWithCUMask.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint32,
-                                                 ctypes.POINTER(ctypes.c_uint32)]
-    hip.hipStreamSynchronize.argtypes = [ctypes.c_void_p]
-    hip.hipStreamDestroy.argtypes = [ctypes.c_void_p]
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     n = 1 << 28
     x = torch.rand(n, device="cuda") * 200 - 100
     y = torch.empty_like(x)
     torch.cuda.synchronize()
-    words = (cus + 31) // 32
     print("| CUs | 2P ms | 2P GB/s (3N) | 3P-recompute ms | 3P-reload ms | 2P vs recompute | 2P vs reload |")
     print("|---|---|---|---|---|---|---|")
     for k in (8, 16, 32, 64, 96, 128, 192, cus):
-        mask = (ctypes.c_uint32 * words)()
-        for i in range(k):
-            mask[i // 32] |= 1 << (i % 32)
-        st = ctypes.c_void_p()
-        rc = hip.hipExtStreamCreateWithCUMask(ctypes.byref(st), words, mask)
-        if rc != 0:
-            sys.exit(f"hipExtStreamCreateWithCUMask failed with {rc}")
-        ms = []
-        for fn in (B.softmax2p_f32, B.softmax3p_recompute_f32, B.softmax3p_reload_f32):
-            w0 = time.perf_counter()
-            warm = 0
-            while warm < 2 or time.perf_counter() - w0 < 0.05:   # untimed; also brings the clocks up
-                fn(x, y, 1, n, stream=st.value)
-                hip.hipStreamSynchronize(st)
-                warm += 1
-            t0 = time.perf_counter()
-            for _ in range(args.iters):
-                fn(x, y, 1, n, stream=st.value)
-            hip.hipStreamSynchronize(st)
-            ms.append((time.perf_counter() - t0) / args.iters * 1e3)
+        with masked_stream(k, cus) as st:
+            ms = [time_on_stream(lambda s, fn=fn: fn(x, y, 1, n, stream=s), st, args.iters)
+                  for fn in (B.softmax2p_f32, B.softmax3p_recompute_f32, B.softmax3p_reload_f32)]
         print(f"| {k} | {ms[0]:.3f} | {3 * n * 4 / ms[0] / 1e6:.0f} | {ms[1]:.3f} | {ms[2]:.3f} | "
               f"{ms[1] / ms[0]:.2f}x | {ms[2] / ms[0]:.2f}x |", flush=True)
-        hip.hipStreamDestroy(st)
     B.softmax_tp_release()
 
 
