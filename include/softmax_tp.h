@@ -31,8 +31,8 @@
  *            frees it.  The library allocates nothing else.
  *   threads  several host threads may call at once provided no two of them use the
  *            same stream at the same time (two calls interleaved on one stream would
- *            share that stream's workspace).  softmax_tp_tune and
- *            softmax_tp_release must not run concurrently with any other call.
+ *            share that stream's workspace).  softmax_tp_release must not run concurrently
+ *            with any other call; for softmax_tp_tune see there.
  */
 #ifndef SOFTMAX_TP_H
 #define SOFTMAX_TP_H
@@ -253,7 +253,9 @@ TP_API int softmax_tp_plan(int64_t rows, int64_t n, int32_t elem_bytes, int32_t 
  *                     more than that go through a merge kernel first (at most 4096)
  * block is 256, 512 or 1024; unroll 2, 4 or 8 (16-bit formats: 2 or 4); in addition the
  * pair block 128, unroll 1.  value 0 restores the
- * default.  Not thread safe against running calls.
+ * default.  May be called while other threads plan or launch (each call reads the settings
+ * under a lock and sees every key either before or after the change), but a call that
+ * overlaps a retune may mix old and new keys: retune between calls when that matters.
  */
 TP_API int softmax_tp_tune(const char *key, int64_t value);
 

@@ -27,7 +27,17 @@ struct Tuning {
     int64_t nt_first = 0;
     int64_t fold_max = 0;
 };
-static Tuning g_tune;
+// Written by softmax_tp_tune only; every reader takes a copy under the lock, so a sweep thread
+// that retunes while another thread plans or launches is not a data race (the call then sees
+// either the old or the new value of each key).
+static Tuning g_tune_shared;
+static std::mutex g_tune_mutex;
+
+static Tuning tuning()
+{
+    std::lock_guard<std::mutex> lock(g_tune_mutex);
+    return g_tune_shared;
+}
 
 constexpr int64_t kRowsPathMaxBytes = 256 * 1024;  // longest row one workgroup takes
 constexpr int64_t kRowsPathMinRows = 32;           // fewer rows than this cannot fill the chip
@@ -54,7 +64,7 @@ static bool valid_unroll(int64_t u, int elem_bytes)
 // most 15 % of its last round on the row.
 constexpr int64_t kWaveRowMaxVecs = 256;  // rows up to this many vectors get a wave each
 
-static void rows_shape(int64_t nvec, int elem_bytes, softmax_tp_shape_t *s)
+static void rows_shape(const Tuning &g_tune, int64_t nvec, int elem_bytes, softmax_tp_shape_t *s)
 {
     s->chunk_vecs = 0;
     s->chunks = 1;
@@ -120,6 +130,7 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
     std::memset(p, 0, sizeof *p);
     if (rows == 0 || n == 0)
         return TP_OK;
+    const Tuning g_tune = tuning();
     if (n > INT64_MAX / elem_bytes / rows)
         return TP_ERR_TOO_LARGE;
     const int V = congruent16 ? 16 / elem_bytes : 1;
@@ -137,7 +148,7 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
         if (rows > kGridMax || nvec > kChunkVecsMax)
             return TP_ERR_TOO_LARGE;
         p->path = 1;
-        rows_shape(nvec, elem_bytes, &p->rows);
+        rows_shape(g_tune, nvec, elem_bytes, &p->rows);
         // one workgroup per row (a wave-per-row launch has a quarter of the workgroups)
         const int64_t threads = p->rows.block == kWave ? kWave : p->rows.block;
         if (rows > kThreadsMax / threads)
@@ -270,13 +281,17 @@ static dim3 chunk_grid(int64_t rows, const softmax_tp_shape_t &s)
     return dim3((uint32_t)((total + kXcds - 1) / kXcds * kXcds));
 }
 
-static int fold_max() { return g_tune.fold_max ? (int)g_tune.fold_max : kFoldMax; }
+static int fold_max()
+{
+    const int64_t f = tuning().fold_max;
+    return f ? (int)f : kFoldMax;
+}
 
 // Every pass walks memory forwards.  With the tuning key "direction" = 2, pass k of a call
 // (0-based) runs backwards when k is odd, so that it starts on what the previous pass touched
 // last; on this part that measured the same or slightly worse, the caches being small next to
 // the arrays that take this path.
-static bool pass_reversed(int k) { return g_tune.direction == 2 && (k & 1) != 0; }
+static bool pass_reversed(int k) { return tuning().direction == 2 && (k & 1) != 0; }
 
 template <int N>
 using ic = std::integral_constant<int, N>;
@@ -933,22 +948,23 @@ int softmax_tp_tune(const char *key, int64_t value)
         int64_t *slot;
         int kind;
     } keys[] = {
-        {"path", &g_tune.path, kThree},
-        {"block_rows", &g_tune.block_rows, kBlock},
-        {"unroll_rows", &g_tune.unroll_rows, kUnroll},
-        {"block_reduce", &g_tune.block_reduce, kBlock},
-        {"unroll_reduce", &g_tune.unroll_reduce, kUnroll},
-        {"target_reduce", &g_tune.target_reduce, kAny},
-        {"block_map", &g_tune.block_map, kBlock},
-        {"unroll_map", &g_tune.unroll_map, kUnroll},
-        {"tiles_map", &g_tune.tiles_map, kAny},
-        {"block_mapsum", &g_tune.block_mapsum, kBlock},
-        {"unroll_mapsum", &g_tune.unroll_mapsum, kUnroll},
-        {"tiles_mapsum", &g_tune.tiles_mapsum, kAny},
-        {"direction", &g_tune.direction, kThree},
-        {"nt_first", &g_tune.nt_first, kThree},
-        {"fold_max", &g_tune.fold_max, kAny},
+        {"path", &g_tune_shared.path, kThree},
+        {"block_rows", &g_tune_shared.block_rows, kBlock},
+        {"unroll_rows", &g_tune_shared.unroll_rows, kUnroll},
+        {"block_reduce", &g_tune_shared.block_reduce, kBlock},
+        {"unroll_reduce", &g_tune_shared.unroll_reduce, kUnroll},
+        {"target_reduce", &g_tune_shared.target_reduce, kAny},
+        {"block_map", &g_tune_shared.block_map, kBlock},
+        {"unroll_map", &g_tune_shared.unroll_map, kUnroll},
+        {"tiles_map", &g_tune_shared.tiles_map, kAny},
+        {"block_mapsum", &g_tune_shared.block_mapsum, kBlock},
+        {"unroll_mapsum", &g_tune_shared.unroll_mapsum, kUnroll},
+        {"tiles_mapsum", &g_tune_shared.tiles_mapsum, kAny},
+        {"direction", &g_tune_shared.direction, kThree},
+        {"nt_first", &g_tune_shared.nt_first, kThree},
+        {"fold_max", &g_tune_shared.fold_max, kAny},
     };
+    std::lock_guard<std::mutex> lock(g_tune_mutex);
     for (auto &k : keys) {
         if (std::strcmp(key, k.name) != 0)
             continue;
@@ -956,7 +972,7 @@ int softmax_tp_tune(const char *key, int64_t value)
             if (k.kind == kBlock && !valid_block(value)) return TP_ERR_TUNING;
             if (k.kind == kUnroll && !valid_unroll(value, 4)) return TP_ERR_TUNING;
             if (k.kind == kThree && value > 2) return TP_ERR_TUNING;
-            if (k.slot == &g_tune.fold_max && value > 4096) return TP_ERR_TUNING;
+            if (k.slot == &g_tune_shared.fold_max && value > 4096) return TP_ERR_TUNING;
         }
         *k.slot = value;
         return TP_OK;

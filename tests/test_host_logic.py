@@ -170,6 +170,37 @@ def test_tuning_keys(B):
     assert B.softmax_tp_plan(1, 1 << 28).map.block == 128
 
 
+def test_retuning_while_another_thread_plans(B):
+    """softmax_tp_tune from one thread while others plan: every plan is one a single setting would
+    give (the settings are read under a lock), nothing crashes."""
+    import threading
+    stop = threading.Event()
+    seen, errors = set(), []
+
+    def planner():
+        try:
+            while not stop.is_set():
+                p = B.softmax_tp_plan(2, 10_000_000)
+                seen.add((p.map.block, p.map.unroll))
+        except Exception as e:   # noqa: BLE001
+            errors.append(e)
+
+    threads = [threading.Thread(target=planner) for _ in range(3)]
+    for t in threads:
+        t.start()
+    try:
+        for i in range(3000):
+            B.softmax_tp_tune("block_map", (256, 512, 1024)[i % 3])
+            B.softmax_tp_tune("unroll_map", (2, 4)[i % 2])
+    finally:
+        stop.set()
+        for t in threads:
+            t.join()
+        B.softmax_tp_tune_reset()
+    assert not errors
+    assert seen and seen <= {(b, u) for b in (256, 512, 1024) for u in (2, 4)}
+
+
 def test_constants_header_is_what_the_generator_writes(tmp_path):
     csrc = os.path.join(ROOT, "paper_2001_04438_amd", "csrc")
     committed = open(os.path.join(csrc, "expconst.h")).read()
