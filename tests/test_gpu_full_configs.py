@@ -98,4 +98,7 @@ def test_full_size_16bit_long_vector(gpu, oracle_mod, fmt):
     c = oracle_mod.compare(x, y, tol, **kw)
     print(f"cfg4 as {fmt}: max_rel_err={c.max_rel_err:.3e} normal={c.n_normal}", flush=True)
     assert c.n_total == x.size and c.ok(), c.as_dict()
-    assert c.n_normal > 1000
+    # results held to the relative bound: bf16 shares the fp32 exponent range, so every outlier
+    # within about 80 of the largest counts (some 43 thousand of the 268 thousand spread over
+    # [500, 1000]); fp16's smallest normal is 2^-14, which only the top few units of that range reach
+    assert c.n_normal > (30_000 if fmt == "bf16" else 1_000), c.n_normal
