@@ -13,7 +13,7 @@ workload, with the input already resident in HBM.  Prints ONE JSON line:
                    call timed on its own: median and minimum (the protocol of Section 6.2)
   variants         Three-Pass baselines on the same input (4 N s and 5 N s bytes)
   parity           every variant's output on the headline input against the oracle
-  calibration      read / copy / scale streams at 1 GiB (the STREAM comparison of
+  calibration      read / fill / copy / scale streams at 1 GiB (the STREAM comparison of
                    Section 6.4)
   other_workloads  the remaining configurations, each with all variants
 
@@ -333,6 +333,7 @@ def calibration(torch, B, steps, warmup):
     res = {}
     for name, fn, nbytes in (
             ("read", lambda i: B.softmax_tp_stream_read_f32(x, sink, n), 4 * n),
+            ("fill", lambda i: B.softmax_tp_stream_fill_f32(y, 0.5, n), 4 * n),
             ("copy", lambda i: B.softmax_tp_stream_copy_f32(x, y, n), 8 * n),
             ("scale", lambda i: B.softmax_tp_stream_scale_f32(x, y, 0.5, n), 8 * n)):
         for i in range(warmup):
@@ -497,6 +498,9 @@ def main():
             result["vs_calibration"] = {
                 "pass1_over_stream_read": cal["read"]["ms"] / head["pass1_ms"]["avg"],
                 "pass2_over_stream_copy": cal["copy"]["ms"] / head["pass2_ms"]["avg"],
+                # reads and writes do not overlap in the memory system: a copy takes as long as the
+                # read-only and the write-only stream of its size one after the other
+                "copy_over_read_plus_fill": cal["copy"]["ms"] / (cal["read"]["ms"] + cal["fill"]["ms"]),
                 "call_over_read_plus_copy": (cal["read"]["ms"] + cal["copy"]["ms"]) / two["ms_per_step"]}
         others = {}
         for name in ("cfg2", "cfg3", "cfg4", "cfg5", "cfg5_f16"):

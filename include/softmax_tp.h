@@ -199,9 +199,12 @@ TP_API int softmax2p_f32_pass2(const float *x, const float *pairs, float *y, int
 /*
  * Bandwidth calibration in the manner of the STREAM comparison of Section 6.4,
  * using the same streaming code as the softmax passes: read `count` floats
- * (their sum goes to sink[0], a device float), copy y = x, scale y = a * x.
+ * (their sum goes to sink[0], a device float), copy y = x, scale y = a * x, and a
+ * write-only stream y = value (a pass that reads and writes takes as long as the read-only
+ * and the write-only stream of its size together, so both ceilings are worth knowing).
  */
 TP_API int softmax_tp_stream_read_f32(const float *x, float *sink, int64_t count, void *stream);
+TP_API int softmax_tp_stream_fill_f32(float *y, float value, int64_t count, void *stream);
 TP_API int softmax_tp_stream_copy_f32(const float *x, float *y, int64_t count, void *stream);
 TP_API int softmax_tp_stream_scale_f32(const float *x, float *y, float a, int64_t count, void *stream);
 

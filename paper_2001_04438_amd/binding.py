@@ -40,6 +40,7 @@ ENTRY_POINTS = {
     "softmax2p_f32_pass1": [_vp, _vp, _i64, _i64, _vp],
     "softmax2p_f32_pass2": [_vp, _vp, _vp, _i64, _i64, _vp],
     "softmax_tp_stream_read_f32": [_vp, _vp, _i64, _vp],
+    "softmax_tp_stream_fill_f32": [_vp, ctypes.c_float, _i64, _vp],
     "softmax_tp_stream_copy_f32": [_vp, _vp, _i64, _vp],
     "softmax_tp_stream_scale_f32": [_vp, _vp, ctypes.c_float, _i64, _vp],
     "softmax_tp_plan": [_i64, _i64, ctypes.c_int32, ctypes.c_int32, _vp],
@@ -241,6 +242,11 @@ def softmax2p_f32_pass2(x, pairs, y, rows, n, stream=None):
 def softmax_tp_stream_read_f32(x, sink, count, stream=None):
     _check("softmax_tp_stream_read_f32",
            lib().softmax_tp_stream_read_f32(_addr(x), _addr(sink), count, _stream(stream)))
+
+
+def softmax_tp_stream_fill_f32(y, value, count, stream=None):
+    _check("softmax_tp_stream_fill_f32",
+           lib().softmax_tp_stream_fill_f32(_addr(y), float(value), count, _stream(stream)))
 
 
 def softmax_tp_stream_copy_f32(x, y, count, stream=None):

@@ -849,6 +849,21 @@ int softmax_tp_stream_copy_f32(const float *x, float *y, int64_t count, void *st
     });
 }
 
+int softmax_tp_stream_fill_f32(float *y, float value, int64_t count, void *stream)
+{
+    int rc = check_args(y, y, 1, count, 4);
+    if (rc != TP_OK || count == 0)
+        return rc;
+    softmax_tp_plan_t plan;
+    if ((rc = make_plan(1, count, 4, true, 2, &plan)) != TP_OK)
+        return rc;
+    const ChunkArgs a = chunk_args(count, plan.map, 1, false);
+    const dim3 grid = chunk_grid(1, plan.map);
+    return with_shape<F32x4>(plan.map, [&](auto B, auto U) {
+        return launch(chunk_fill<TP_B, TP_U>, grid, dim3(TP_B), (hipStream_t)stream, y, a, value);
+    });
+}
+
 int softmax_tp_stream_scale_f32(const float *x, float *y, float scale, int64_t count, void *stream)
 {
     int rc = check_args(x, y, 1, count, 4);

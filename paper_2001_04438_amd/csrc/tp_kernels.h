@@ -536,6 +536,24 @@ __global__ __launch_bounds__(BLOCK) void chunk_copy(const typename IO::elem *x,
     stream<IO, BLOCK, U, kLoadStream, kStoreStream>(s, cp);
 }
 
+// Write-only stream: y = value.  Same chunking and the same stores as the read-write passes.
+template <int BLOCK, int U>
+__global__ __launch_bounds__(BLOCK) void chunk_fill(float *y, ChunkArgs a, float value)
+{
+    TP_CHUNK_PROLOGUE
+    const Seg<F32x4> s = make_seg<F32x4>(y, y, a.n, row, chunk, a.chunk_vecs);
+    const f32x4 v = {value, value, value, value};
+    f32x4 *yb = s.yv + s.vb;
+    for (uint32_t k = threadIdx.x; k < s.cnt; k += BLOCK)
+        st<kStoreStream>(yb + k, v);
+    if (s.edges) {
+        const int64_t nedge = s.head + (s.n - s.tail0);
+        if ((int64_t)threadIdx.x < nedge)
+            s.yrow[(int)threadIdx.x < s.head ? (int64_t)threadIdx.x
+                                              : s.tail0 + ((int64_t)threadIdx.x - s.head)] = value;
+    }
+}
+
 // ---- merges: grid = rows, one workgroup folds the `chunks` partials of its row ----
 
 constexpr int kMergeBlock = 256;

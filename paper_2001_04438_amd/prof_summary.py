@@ -21,6 +21,9 @@ the dispatch list is cut into variants at those markers, so kernels that several
   profiles/kernels_all_workloads.md        durations, bytes, VALU counts of every kernel
   profiles/chunk_2p_pass2_cfg4.md          the dominant kernel of the headline workload
   profiles/memory_side_cfg4.md             the memory-side counters of the 1 GiB streams
+  profiles/bench_kernel_trace.md           kernel durations of the default bench.py run (if DIR/bench.trace,
+                                           made by `rocprofv3 --kernel-trace --stats ... -- python3 bench.py
+                                           --steps 20 --warmup 5 > DIR/bench.trace.json`, is there)
 
     python -m paper_2001_04438_amd.prof_summary DIR [--commit HASH]
 """
@@ -122,9 +125,10 @@ def per_kernel(dispatches, calls, fields):
         groups.setdefault(short(d["kernel"]), []).append(d)
     res = collections.OrderedDict()
     for k, ds in groups.items():
+        us = sorted(d["us"] for d in ds)
         e = {"launches_per_call": len(ds) / calls, "grid_threads": ds[0]["grid"], "block": ds[0]["block"],
-             "us_avg": sum(d["us"] for d in ds) / len(ds), "us_min": min(d["us"] for d in ds),
-             "us_max": max(d["us"] for d in ds), "dispatches": len(ds)}
+             "us_avg": sum(us) / len(us), "us_med": us[len(us) // 2], "us_min": us[0], "us_max": us[-1],
+             "dispatches": len(ds)}
         for f in fields:
             vals = [d[f] for d in ds if f in d]
             if vals:
@@ -222,7 +226,7 @@ def write_kernels_md(data, counters, root, path):
              "variants of that workload: `softmax2p,softmax3p_recompute,softmax3p_reload,copy,read`, on the "
              "workloads with short rows also `softmax2p_onchip,softmax3p_onchip`):\n")
     L.append("```")
-    L.append("rocprofv3 --kernel-trace --stats --output-format csv -d $D/$W.trace -- python3 $R/bench.py --workload $W --calls-only $V --steps 20 --warmup 5 > $D/$W.trace.json")
+    L.append("rocprofv3 --kernel-trace --stats --output-format csv -d $D/$W.trace -- python3 $R/bench.py --workload $W --calls-only $V --steps 300 --warmup 100 > $D/$W.trace.json")
     L.append(f"rocprofv3 --pmc {RD_SET} --output-format csv -d $D/$W.rd -- python3 $R/bench.py --workload $W --calls-only $V --steps 5 --warmup 2 > $D/$W.rd.json")
     L.append("rocprofv3 --pmc WRITE_SIZE --output-format csv -d $D/$W.wr -- python3 $R/bench.py --workload $W --calls-only $V --steps 5 --warmup 2 > $D/$W.wr.json")
     L.append(f"rocprofv3 --pmc {SQ_SET} --output-format csv -d $D/$W.sq -- python3 $R/bench.py --workload $W --calls-only $V --steps 5 --warmup 2 > $D/$W.sq.json")
@@ -232,15 +236,18 @@ def write_kernels_md(data, counters, root, path):
              "fabric: read = 32 x `TCC_EA0_RDREQ_32B` + 64 x `TCC_EA0_RDREQ_64B` + 128 x `TCC_EA0_RDREQ_128B`, "
              "written = `WRITE_SIZE` x 1024.  Hits in the 256 MB memory-side cache are behind that point and not "
              "visible.  VALU = `SQ_INSTS_VALU` (wave instructions) x 64 lanes / elements of the workload.  "
-             "Durations are from the kernel trace (not from the counter runs, which serialise dispatches).\n")
+             "Durations are from the kernel trace (not from the counter runs, which serialise dispatches); the "
+             "first few dozen launches after the host has kept the device idle run at a reduced shader clock "
+             "(1.5 to 2.0 instead of 2.4 GHz, which slows the passes with arithmetic in them by up to a quarter), "
+             "hence 400 calls per variant and the median next to the average.\n")
     for w, wl in data.items():
         info = wl["info"]
         s = ELEM_BYTES[info["dtype"]]
         elems = info["rows"] * info["n"]
         L.append(f"## {w}: {info['rows']} x {info['n']} {info['dtype']} ({elems * s / 2**20:,.1f} MiB in, the same out)\n")
-        L.append("| variant | kernel | launches per call | grid x block | avg us | min | max | MiB read | MiB written | "
-                 "VALU lane-ops per element |")
-        L.append("|---|---|---|---|---|---|---|---|---|---|")
+        L.append("| variant | kernel | launches per call | grid x block | avg us | median | min | max | MiB read | "
+                 "MiB written | VALU lane-ops per element |")
+        L.append("|---|---|---|---|---|---|---|---|---|---|---|")
         for variant, kinds in wl.get("variants", {}).items():
             ref = kinds.get("trace") or kinds.get("rd") or kinds.get("sq") or {}
             for kname, t in ref.items():
@@ -248,10 +255,10 @@ def write_kernels_md(data, counters, root, path):
                 wr = kinds.get("wr", {}).get(kname)
                 sq = kinds.get("sq", {}).get(kname)
                 tr = kinds.get("trace", {}).get(kname)
-                L.append("| {} | `{}` | {:g} | {} x {} | {} | {} | {} | {} | {} | {} |".format(
+                L.append("| {} | `{}` | {:g} | {} x {} | {} | {} | {} | {} | {} | {} | {} |".format(
                     variant, kname, t["launches_per_call"], t["grid_threads"] // max(t["block"], 1), t["block"],
-                    f"{tr['us_avg']:.1f}" if tr else "-", f"{tr['us_min']:.1f}" if tr else "-",
-                    f"{tr['us_max']:.1f}" if tr else "-",
+                    f"{tr['us_avg']:.1f}" if tr else "-", f"{tr['us_med']:.1f}" if tr else "-",
+                    f"{tr['us_min']:.1f}" if tr else "-", f"{tr['us_max']:.1f}" if tr else "-",
                     f"{read_bytes(rd) / 2**20:,.2f}" if rd else "-",
                     f"{wr.get('WRITE_SIZE', 0) / 1024:,.2f}" if wr else "-",
                     f"{sq['SQ_INSTS_VALU'] * 64 / elems:.1f}" if sq and "SQ_INSTS_VALU" in sq else "-"))
@@ -360,20 +367,22 @@ def write_dominant_md(data, counters, path):
     mg = next((tr[k] for k in tr if k.startswith("merge_pairs")), None)
     L = [f"# `{p2}` on cfg4 (1 x 2^28 fp32, 1 GiB in, 1 GiB out): the dominant kernel\n",
          "Commands: as in `kernels_all_workloads.md` with `$W` = cfg4 (`rocprofv3 --kernel-trace --stats ... -- python3 "
-         "bench.py --workload cfg4 --calls-only softmax2p,softmax3p_recompute,softmax3p_reload,copy,read --steps 20 "
-         "--warmup 5`, and the `rd` / `wr` counter runs of the same command with `--steps 5 --warmup 2`).\n",
+         "bench.py --workload cfg4 --calls-only softmax2p,softmax3p_recompute,softmax3p_reload,copy,read --steps 300 "
+         "--warmup 100`, and the `rd` / `wr` counter runs of the same command with `--steps 5 --warmup 2`).\n",
          "| figure | value |", "|---|---|",
          f"| launches in the trace | {t['dispatches']} |",
-         f"| average duration (kernel trace) | {t['us_avg']:.1f} us (min {t['us_min']:.1f}, max {t['us_max']:.1f}) |",
+         f"| average duration (kernel trace) | {t['us_avg']:.1f} us (median {t['us_med']:.1f}, min {t['us_min']:.1f}, "
+         f"max {t['us_max']:.1f}) |",
          f"| algorithmic bytes per launch | 2 * 2^28 * 4 = {alg:,} B (read x once, write y once) |",
-         f"| achieved (algorithmic bytes / trace duration) | {alg / t['us_avg'] / 1e6:.2f} TB/s = "
+         f"| achieved (algorithmic bytes / average duration) | {alg / t['us_avg'] / 1e6:.2f} TB/s = "
          f"{alg / t['us_avg'] / 1e6 / 8 * 100:.1f} % of the 8 TB/s HBM peak |"]
     if "hbm_bytes" in rec:
         L += [f"| bytes read from the memory fabric per launch (request counters) | {rec['fetch_bytes']:,} |",
               f"| bytes written per launch (WRITE_SIZE) | {rec['write_bytes']:,} |",
               f"| measured traffic per launch | {rec['hbm_bytes']:,} B = {rec['hbm_bytes'] / alg:.5f} x algorithmic |"]
     if ck:
-        L.append(f"| plain copy kernel of the same size in the same run (`{next(iter(copy))}`) | {ck['us_avg']:.1f} us |")
+        L.append(f"| plain copy kernel of the same size in the same run (`{next(iter(copy))}`) | {ck['us_avg']:.1f} us "
+                 f"(median {ck['us_med']:.1f}) |")
     L.append("")
     if p1 and mg:
         L.append(f"The whole Two-Pass call on this workload: pass 1 {p1['us_avg']:.1f} us "
@@ -381,6 +390,50 @@ def write_dominant_md(data, counters, path):
                  f"kernel {t['us_avg']:.1f} us.  Durations vary by a few percent from box to box.")
     L.append("")
     open(path, "w").write("\n".join(L))
+
+
+def write_bench_trace_md(root, path):
+    """Kernel durations of the default `bench.py` run under rocprofv3 --kernel-trace --stats (DIR/bench.trace)."""
+    files = glob.glob(os.path.join(root, "bench.trace", "**", "*_kernel_trace.csv"), recursive=True)
+    line = os.path.join(root, "bench.trace.json")
+    if not files or not os.path.exists(line):
+        return False
+    bench = None
+    for text in open(line):
+        if text.startswith("{"):
+            bench = json.loads(text)
+    groups = collections.OrderedDict()
+    for r in csv.DictReader(open(files[0])):
+        if "tp::" not in r["Kernel_Name"]:
+            continue
+        k = (short(r["Kernel_Name"]), int(r["Grid_Size_X"]) // max(int(r["Workgroup_Size_X"]), 1), int(r["Workgroup_Size_X"]))
+        groups.setdefault(k, []).append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
+    L = ["# Kernel trace of the default `bench.py` run (MI355X, gfx950)\n",
+         "Command (from `/tmp` with `TMPDIR=/tmp`; `$R` is the repository root):\n", "```",
+         "rocprofv3 --kernel-trace --stats --output-format csv -d $D/bench.trace -- python3 $R/bench.py --steps 20 --warmup 5 > $D/bench.trace.json",
+         "```\n"]
+    if bench:
+        ro = bench["roofline"]
+        # the headline shape is the instantiation of that kernel the run spent the most time in
+        dom = sorted((v for k, v in groups.items() if k[0].startswith(ro["kernel"] + "<")), key=sum, reverse=True)
+        L.append(f"The same run's JSON line: `value` {bench['value']:.0f} GB/s, `ms_per_step` {bench['ms_per_step']:.4f}, "
+                 f"`roofline.avg_launch_ms` {ro['avg_launch_ms']:.4f} for `{ro['kernel']}` (events, eight launches per "
+                 f"pair), `roofline.frac` {ro['frac']:.3f}; `long_run` median {bench['long_run']['ms_median']:.4f} ms over "
+                 f"{bench['long_run']['calls']} calls.")
+        if dom:
+            us = sorted(dom[0])
+            L.append(f"Kernel trace of that kernel at the headline shape: {len(us)} launches, average "
+                     f"{sum(us) / len(us):.1f} us, median {us[len(us) // 2]:.1f}, min {us[0]:.1f}, max {us[-1]:.1f}: "
+                     f"{ro['algorithmic_bytes_per_launch'] / (sum(us) / len(us)) / 1e6 / 8 * 100:.1f} % of the 8 TB/s peak "
+                     "on its algorithmic bytes.")
+        L.append("")
+    L += ["| kernel | grid (workgroups x threads) | launches | avg us | median | min | max |", "|---|---|---|---|---|---|---|"]
+    for (k, g, b), us in sorted(groups.items(), key=lambda kv: -sum(kv[1])):
+        us = sorted(us)
+        L.append(f"| `{k}` | {g} x {b} | {len(us)} | {sum(us) / len(us):.1f} | {us[len(us) // 2]:.1f} | {us[0]:.1f} | {us[-1]:.1f} |")
+    L.append("")
+    open(path, "w").write("\n".join(L))
+    return True
 
 
 def main():
@@ -399,7 +452,8 @@ def main():
     write_kernels_md(data, counters, args.dir, os.path.join(PROFILES, "kernels_all_workloads.md"))
     write_dominant_md(data, counters, os.path.join(PROFILES, "chunk_2p_pass2_cfg4.md"))
     write_memory_md(data, os.path.join(PROFILES, "memory_side_cfg4.md"))
-    print("wrote profiles/counters.json, kernels_all_workloads.md, chunk_2p_pass2_cfg4.md, memory_side_cfg4.md")
+    extra = ", bench_kernel_trace.md" if write_bench_trace_md(args.dir, os.path.join(PROFILES, "bench_kernel_trace.md")) else ""
+    print("wrote profiles/counters.json, kernels_all_workloads.md, chunk_2p_pass2_cfg4.md, memory_side_cfg4.md" + extra)
 
 
 if __name__ == "__main__":

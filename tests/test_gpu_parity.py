@@ -771,5 +771,10 @@ def test_calibration_streams(gpu):
     assert torch.equal(x, y)
     gpu.softmax_tp_stream_scale_f32(x, y, 2.5, n)
     assert torch.equal(x * 2.5, y)
+    for off in (0, 1, 3):                               # 16-byte aligned or not: nothing outside is touched
+        buf = torch.full((n + 8,), -7.0, dtype=torch.float32, device="cuda")
+        gpu.softmax_tp_stream_fill_f32(buf[off:off + n], 1.25, n)
+        assert bool((buf[off:off + n] == 1.25).all()) and bool((buf[:off] == -7).all()) \
+            and bool((buf[off + n:] == -7).all())
     gpu.softmax_tp_stream_read_f32(x, sink, n)
     assert abs(float(sink[0]) - float(x.double().sum())) <= 1e-6 * float(x.double().sum())
