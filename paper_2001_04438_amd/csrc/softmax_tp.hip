@@ -62,14 +62,21 @@ static bool valid_unroll(int64_t u, int elem_bytes)
 
 // Rows path: the largest tile (block * unroll vectors per round) that wastes at
 // most 15 % of its last round on the row.
-constexpr int64_t kWaveRowMaxVecs = 256;  // rows up to this many vectors get a wave each
+constexpr int64_t kWaveRowMaxVecs = 256;  // rows up to this many vectors get a wave each ...
+constexpr int64_t kQuadRowMaxVecs = 64;   // ... and up to this many a row of 16 lanes (shape.block 16)
+constexpr int kQuad = 16;
 
 static void rows_shape(const Tuning &g_tune, int64_t nvec, int elem_bytes, softmax_tp_shape_t *s)
 {
     s->chunk_vecs = 0;
     s->chunks = 1;
+    if (nvec <= kQuadRowMaxVecs && !g_tune.block_rows && !g_tune.unroll_rows) {
+        s->block = kQuad;  // sixteen lanes per row, sixteen rows per workgroup
+        s->unroll = nvec <= kQuad ? 1 : nvec <= 2 * kQuad ? 2 : 4;
+        return;
+    }
     if (nvec <= kWaveRowMaxVecs && !g_tune.block_rows && !g_tune.unroll_rows) {
-        s->block = kWave;  // one wave per row, kWavesPerGroup rows per workgroup
+        s->block = kWave;  // one wave per row, four rows per workgroup
         s->unroll = nvec <= 2 * kWave ? 2 : 4;
         return;
     }
@@ -149,12 +156,11 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
             return TP_ERR_TOO_LARGE;
         p->path = 1;
         rows_shape(g_tune, nvec, elem_bytes, &p->rows);
-        // one workgroup per row (a wave-per-row launch has a quarter of the workgroups)
-        const int64_t threads = p->rows.block == kWave ? kWave : p->rows.block;
-        if (rows > kThreadsMax / threads)
+        // rows.block threads per row, whether that is a workgroup, a wave or a row of 16 lanes
+        if (rows > kThreadsMax / p->rows.block)
             return TP_ERR_TOO_LARGE;
         p->launches = 1;
-        return (p->rows.block == kWave || valid_block(p->rows.block)) &&
+        return (p->rows.block == kWave || p->rows.block == kQuad || valid_block(p->rows.block)) &&
                        valid_unroll(p->rows.unroll, elem_bytes)
                    ? TP_OK : TP_ERR_TUNING;
     }
@@ -329,17 +335,23 @@ template <class IO>
 static int run_rows(Algo algo, const softmax_tp_plan_t &plan, const typename IO::elem *x,
                     typename IO::elem *y, int64_t rows, int64_t n, hipStream_t st)
 {
-    if (plan.rows.block == kWave) {  // short rows: a wave per row
-        const dim3 wgrid((uint32_t)((rows + kWavesPerGroup - 1) / kWavesPerGroup));
-        const dim3 wblock(kWave * kWavesPerGroup);
-        auto waves = [&](auto U) {
+    if (plan.rows.block == kWave || plan.rows.block == kQuad) {  // short rows: a lane group per row
+        const int64_t per_group = kShortBlock / plan.rows.block;
+        const dim3 wgrid((uint32_t)((rows + per_group - 1) / per_group));
+        const dim3 wblock(kShortBlock);
+        auto go = [&](auto LANES, auto U) {
+            constexpr int L = decltype(LANES)::value;
             if (algo == kTwoPass)
-                return launch(waves_2p<IO, TP_U>, wgrid, wblock, st, x, y, n, rows);
+                return launch(waves_2p<IO, L, TP_U>, wgrid, wblock, st, x, y, n, rows);
             if (algo == kRecompute)
-                return launch(waves_3p_recompute<IO, TP_U>, wgrid, wblock, st, x, y, n, rows);
-            return launch(waves_3p_reload<IO, TP_U>, wgrid, wblock, st, x, y, n, rows);
+                return launch(waves_3p_recompute<IO, L, TP_U>, wgrid, wblock, st, x, y, n, rows);
+            return launch(waves_3p_reload<IO, L, TP_U>, wgrid, wblock, st, x, y, n, rows);
         };
-        return plan.rows.unroll == 2 ? waves(ic<2>{}) : waves(ic<4>{});
+        if (plan.rows.block == kWave)
+            return plan.rows.unroll == 2 ? go(ic<kWave>{}, ic<2>{}) : go(ic<kWave>{}, ic<4>{});
+        return plan.rows.unroll == 1   ? go(ic<kQuad>{}, ic<1>{})
+               : plan.rows.unroll == 2 ? go(ic<kQuad>{}, ic<2>{})
+                                       : go(ic<kQuad>{}, ic<4>{});
     }
     const dim3 grid((uint32_t)rows);
     return with_shape<IO>(plan.rows, [&](auto B, auto U) {

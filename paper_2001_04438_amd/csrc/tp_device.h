@@ -132,6 +132,36 @@ __device__ __forceinline__ void wave_pair(float &m, float &n)
     n = nw;
 }
 
+// The same reductions over LANES = 64 (the wave) or LANES = 16 (each row of 16 lanes on its own,
+// four independent results per wave: the DPP butterfly alone, no cross-row step).
+template <int LANES>
+__device__ __forceinline__ float lanes_max(float v)
+{
+    static_assert(LANES == 64 || LANES == 16, "a wave or a row of 16 lanes");
+    if constexpr (LANES == 64)
+        return wave_max(v);
+    TP_ROW_BUTTERFLY(v, op_max)
+    return v;
+}
+
+template <int LANES>
+__device__ __forceinline__ float lanes_sum(float v)
+{
+    static_assert(LANES == 64 || LANES == 16, "a wave or a row of 16 lanes");
+    if constexpr (LANES == 64)
+        return wave_sum(v);
+    TP_ROW_BUTTERFLY(v, op_add)
+    return v;
+}
+
+template <int LANES>
+__device__ __forceinline__ void lanes_pair(float &m, float &n)
+{
+    const float nw = lanes_max<LANES>(n);
+    m = lanes_sum<LANES>(scale_pow2(m, n - nw));
+    n = nw;
+}
+
 // A row's partial results folded by every wave on its own: lane i takes partials i,
 // i + 64, ... in that order, then the wave reduction.  No LDS, no barrier, and every wave of
 // every workgroup gets the bit-identical value.  The partials are read by all the waves of a

@@ -70,62 +70,65 @@ __global__ __launch_bounds__(BLOCK) void rows_3p_reload(const typename IO::elem 
     stream<IO, BLOCK, U, kLoadStream, kStoreStream>(sy, sc);
 }
 
-// ---- short rows: one wave per row, several rows per workgroup --------------------------
+// ---- short rows: LANES lanes per row, several rows per workgroup -----------------------
 //
-// Rows of at most a few hundred vectors cannot keep a whole workgroup busy.  Here every
-// wave owns a row of its own: no LDS, no barrier, the wave reduction is the row reduction.
+// Rows of at most a few hundred vectors cannot keep a whole workgroup busy.  Here a group of
+// LANES lanes owns a row of its own: no LDS, no barrier, the lane-group reduction is the row
+// reduction.  LANES = 64: one wave per row, four rows per workgroup.  LANES = 16, for rows of
+// at most 64 vectors: one 16-lane DPP row per softmax row, sixteen rows per workgroup, so the
+// per-row cost of reductions and addressing is shared by four rows per wave instruction.
 
-constexpr int kWavesPerGroup = 4;
+constexpr int kShortBlock = 256;
 
-#define TP_WAVE_ROW_PROLOGUE                                                                 \
-    const int64_t row = (int64_t)blockIdx.x * kWavesPerGroup + threadIdx.x / kWave;          \
+#define TP_SHORT_ROW_PROLOGUE                                                                \
+    const int64_t row = (int64_t)blockIdx.x * (kShortBlock / LANES) + threadIdx.x / LANES;   \
     if (row >= rows)                                                                         \
         return;                                                                              \
-    const uint32_t lane = threadIdx.x & (kWave - 1);                                         \
+    const uint32_t lane = threadIdx.x & (LANES - 1);                                         \
     const Seg<IO> s = make_seg<IO>(x, y, n, row, 0, INT64_MAX / 2);
 
-template <class IO, int U>
-__global__ __launch_bounds__(kWave *kWavesPerGroup) void waves_2p(const typename IO::elem *x,
-                                                                   typename IO::elem *y,
-                                                                   int64_t n, int64_t rows)
+template <class IO, int LANES, int U>
+__global__ __launch_bounds__(kShortBlock) void waves_2p(const typename IO::elem *x,
+                                                        typename IO::elem *y, int64_t n,
+                                                        int64_t rows)
 {
-    TP_WAVE_ROW_PROLOGUE
+    TP_SHORT_ROW_PROLOGUE
     PairSumOf<IO> acc;
-    stream<IO, kWave, U, kLoadKeep, kStoreStream>(s, acc, lane);
+    stream<IO, LANES, U, kLoadKeep, kStoreStream>(s, acc, lane);
     float m_sum, n_sum;
     acc.finish(m_sum, n_sum);
-    wave_pair(m_sum, n_sum);
+    lanes_pair<LANES>(m_sum, n_sum);
     PairOutOf<IO> out(1.0f / m_sum, n_sum);
-    stream<IO, kWave, U, kLoadStream, kStoreStream>(s, out, lane);
+    stream<IO, LANES, U, kLoadStream, kStoreStream>(s, out, lane);
 }
 
-template <class IO, int U>
-__global__ __launch_bounds__(kWave *kWavesPerGroup) void waves_3p_recompute(
+template <class IO, int LANES, int U>
+__global__ __launch_bounds__(kShortBlock) void waves_3p_recompute(
     const typename IO::elem *x, typename IO::elem *y, int64_t n, int64_t rows)
 {
-    TP_WAVE_ROW_PROLOGUE
+    TP_SHORT_ROW_PROLOGUE
     MaxOf mx;
-    stream<IO, kWave, U, kLoadKeep, kStoreStream>(s, mx, lane);
-    const float mu = wave_max(mx.mx);
+    stream<IO, LANES, U, kLoadKeep, kStoreStream>(s, mx, lane);
+    const float mu = lanes_max<LANES>(mx.mx);
     SumExp<IO::kIntExp> se{mu};
-    stream<IO, kWave, U, kLoadKeep, kStoreStream>(s, se, lane);
-    ExpScale<IO::kIntExp> es(mu, 1.0f / wave_sum(se.s));
-    stream<IO, kWave, U, kLoadStream, kStoreStream>(s, es, lane);
+    stream<IO, LANES, U, kLoadKeep, kStoreStream>(s, se, lane);
+    ExpScale<IO::kIntExp> es(mu, 1.0f / lanes_sum<LANES>(se.s));
+    stream<IO, LANES, U, kLoadStream, kStoreStream>(s, es, lane);
 }
 
-template <class IO, int U>
-__global__ __launch_bounds__(kWave *kWavesPerGroup) void waves_3p_reload(
+template <class IO, int LANES, int U>
+__global__ __launch_bounds__(kShortBlock) void waves_3p_reload(
     const typename IO::elem *x, typename IO::elem *y, int64_t n, int64_t rows)
 {
-    TP_WAVE_ROW_PROLOGUE
+    TP_SHORT_ROW_PROLOGUE
     MaxOf mx;
-    stream<IO, kWave, U, kLoadKeep, kStoreStream>(s, mx, lane);
-    const float mu = wave_max(mx.mx);
+    stream<IO, LANES, U, kLoadKeep, kStoreStream>(s, mx, lane);
+    const float mu = lanes_max<LANES>(mx.mx);
     ExpStoreSum<IO::kIntExp> ess{mu};
-    stream<IO, kWave, U, kLoadStream, kStoreKeep>(s, ess, lane);
+    stream<IO, LANES, U, kLoadStream, kStoreKeep>(s, ess, lane);
     const Seg<IO> sy = make_seg<IO>(y, y, n, row, 0, INT64_MAX / 2);
-    Scale sc{1.0f / wave_sum(ess.s)};
-    stream<IO, kWave, U, kLoadStream, kStoreStream>(sy, sc, lane);
+    Scale sc{1.0f / lanes_sum<LANES>(ess.s)};
+    stream<IO, LANES, U, kLoadStream, kStoreStream>(sy, sc, lane);
 }
 
 // ---- on-chip rows: the row stays in registers between the passes -------------------
