@@ -616,11 +616,28 @@ static int run_onchip(int algo, const typename IO::elem *x, typename IO::elem *y
         return TP_ERR_ALIGN;
     const bool exact = ((uintptr_t)x % 16) == 0 && n % V == 0;
     const int64_t hi = (n + V - 1) / V;
+    hipStream_t st = (hipStream_t)stream;
+    if (hi <= kWaveRowMaxVecs) {  // short rows: a lane group per row, as on the rows path
+        if (rows > kThreadsMax / kWave)
+            return TP_ERR_TOO_LARGE;
+        const int lanes = hi <= kQuadRowMaxVecs ? kQuad : kWave;
+        const int64_t per_group = kShortBlock / lanes;
+        const dim3 wgrid((uint32_t)((rows + per_group - 1) / per_group)), wblock(kShortBlock);
+        auto go = [&](auto LANES, auto U) {
+            constexpr int L = decltype(LANES)::value;
+            if (algo == kOnchipTwoPass)
+                return launch(waves_onchip<IO, L, TP_U, kOnchipTwoPass>, wgrid, wblock, st, x, y, n, rows);
+            return launch(waves_onchip<IO, L, TP_U, kOnchipThreePass>, wgrid, wblock, st, x, y, n, rows);
+        };
+        const int64_t u = (hi + lanes - 1) / lanes;
+        if (lanes == kQuad)
+            return u <= 1 ? go(ic<kQuad>{}, ic<1>{}) : u <= 2 ? go(ic<kQuad>{}, ic<2>{}) : go(ic<kQuad>{}, ic<4>{});
+        return u <= 2 ? go(ic<kWave>{}, ic<2>{}) : go(ic<kWave>{}, ic<4>{});
+    }
     const int64_t lo = exact ? n / V : (n / V > 0 ? n / V - 1 : 0);
     OnchipShape sh;
     if (!onchip_shape(lo, hi, exact, umax, &sh) || rows > kGridMax || rows > kThreadsMax / 1024)
         return TP_ERR_TOO_LARGE;
-    hipStream_t st = (hipStream_t)stream;
 #define TP_OC(B, UU)                                                              \
     case B * 16 + UU:                                                             \
         if constexpr (UU <= umax)                                                 \

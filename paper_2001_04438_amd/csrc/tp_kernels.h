@@ -387,6 +387,109 @@ __global__ __launch_bounds__(BLOCK) void rows_onchip(const typename IO::elem *x,
     onchip_row<IO, BLOCK, U, MODE, ALGO>(s, cur, lds);
 }
 
+// The on-chip arrangement for short rows: LANES lanes (a wave, or a row of 16 lanes) hold a
+// softmax row of at most LANES * U vectors in their registers; reductions as in waves_*.
+template <class IO, int LANES, int U, int ALGO>
+__global__ __launch_bounds__(kShortBlock) void waves_onchip(const typename IO::elem *x,
+                                                            typename IO::elem *y, int64_t n,
+                                                            int64_t rows)
+{
+    TP_SHORT_ROW_PROLOGUE
+    constexpr int V = IO::V;
+    const typename IO::vec *xb = s.xv + s.vb;
+    typename IO::vec *yb = s.yv + s.vb;
+    typename IO::vec v[U];
+    bool own[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        own[u] = lane + (uint32_t)(u * LANES) < s.cnt;
+        v[u] = own[u] ? ld<kLoadStream>(xb + lane + u * LANES) : IO::zero();
+    }
+    const int64_t nedge = s.head + (s.n - s.tail0);
+    const bool edge = (int64_t)lane < nedge;
+    const int64_t iedge = (int)lane < s.head ? (int64_t)lane : s.tail0 + ((int64_t)lane - s.head);
+    const float x_edge = edge ? IO::load1(s.xrow + iedge) : 0.f;
+    float e[U * V], e_edge = 0.f;
+    if constexpr (ALGO == kOnchipTwoPass) {
+        using Acc = PairSumOf<IO>;
+        Acc acc;
+        typename Acc::token g[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (own[u]) {
+                float f[V];
+                IO::unpack(v[u], f);
+                acc.template group<V>(f, e + u * V);
+            }
+            g[u] = acc.exponent();
+        }
+        if (edge)
+            acc.template group<1>(&x_edge, &e_edge);
+        const typename Acc::token g_edge = acc.exponent();
+        float m_sum, n_sum;
+        acc.finish(m_sum, n_sum);
+        lanes_pair<LANES>(m_sum, n_sum);
+        const float lambda = 1.0f / m_sum;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (own[u]) {
+                const float sc = Acc::factor(lambda, g[u], n_sum);
+                float o[V];
+#pragma unroll
+                for (int i = 0; i < V; ++i)
+                    o[i] = e[u * V + i] * sc;
+                st<kStoreStream>(yb + lane + u * LANES, IO::pack(o));
+            }
+        }
+        if (edge)
+            IO::store1(s.yrow + iedge, e_edge * Acc::factor(lambda, g_edge, n_sum));
+    } else {
+        float mx = -__builtin_inff();
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (own[u]) {
+                float f[V];
+                IO::unpack(v[u], f);
+#pragma unroll
+                for (int i = 0; i < V; ++i)
+                    mx = fmaxf(mx, f[i]);
+            }
+        }
+        if (edge)
+            mx = fmaxf(mx, x_edge);
+        const float mu = lanes_max<LANES>(mx);
+        float part = 0.f;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (own[u]) {
+                float f[V], t[V];
+                IO::unpack(v[u], f);
+#pragma unroll
+                for (int i = 0; i < V; ++i)
+                    t[i] = e[u * V + i] = exp_nonpos_as<IO::kIntExp>(f[i] - mu);
+                part += tree_sum<V>(t);
+            }
+        }
+        if (edge) {
+            e_edge = exp_nonpos_as<IO::kIntExp>(x_edge - mu);
+            part += e_edge;
+        }
+        const float lambda = 1.0f / lanes_sum<LANES>(part);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (own[u]) {
+                float o[V];
+#pragma unroll
+                for (int i = 0; i < V; ++i)
+                    o[i] = lambda * e[u * V + i];
+                st<kStoreStream>(yb + lane + u * LANES, IO::pack(o));
+            }
+        }
+        if (edge)
+            IO::store1(s.yrow + iedge, lambda * e_edge);
+    }
+}
+
 // ---- chunk path: grid = rows * chunks, rounded up to a multiple of kXcds ---------
 
 struct ChunkArgs {
