@@ -287,3 +287,54 @@ def test_header_is_plain_c_and_cxx(tmp_path):
                     "-l:libsoftmax_tp.so", "-Wl,-rpath," + lib_dir], check=True)
     out = subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout.split("\n")
     assert out[0] == "0 2 3 0" and out[1].startswith("pointer")
+
+
+def test_prof_summary_cuts_a_counter_file_into_variants(tmp_path, monkeypatch):
+    """prof_summary on a hand-made rocprofv3 counter file: dispatches are attributed to the variant
+    whose marker kernel precedes them, bytes come from the request-size counters, VALU per element
+    from SQ_INSTS_VALU."""
+    from paper_2001_04438_amd import prof_summary as P
+    head = ('"Correlation_Id","Dispatch_Id","Agent_Id","Queue_Id","Process_Id","Thread_Id","Grid_Size","Kernel_Id",'
+            '"Kernel_Name","Workgroup_Size","LDS_Block_Size","Scratch_Size","VGPR_Count","Accum_VGPR_Count",'
+            '"SGPR_Count","Counter_Name","Counter_Value","Start_Timestamp","End_Timestamp"\n')
+    marker = "void tp::extexp_kernel<false>(float const*, float*, float*, long)"
+    two = "void tp::rows_2p<tp::F32x4, 1024, 8>(tp::F32x4::elem const*, tp::F32x4::elem*, long)"
+    mx = "void tp::chunk_max<tp::F32x4, 256, 4, false>(tp::F32x4::elem const*, tp::ChunkArgs, float*)"
+
+    def rows(disp, kernel, counters):
+        return "".join(f'{disp},{disp},"Agent 1",1,1,1,4096,7,"{kernel}",256,0,0,32,0,16,"{c}",{v},{1000 * disp},{1000 * disp + 500}\n'
+                       for c, v in counters.items())
+
+    def run(kind, per_kernel):
+        d = tmp_path / f"cfg2.{kind}" / "host"
+        d.mkdir(parents=True)
+        text, disp = head, 0
+        for variant, kernel in (("softmax2p", two), ("softmax3p_recompute", mx)):
+            disp += 1
+            text += rows(disp, marker, {k: 0 for k in per_kernel(marker)})
+            for _ in range(2):                       # two calls per variant
+                disp += 1
+                text += rows(disp, kernel, per_kernel(kernel))
+        (d / "1_counter_collection.csv").write_text(text)
+        (tmp_path / f"cfg2.{kind}.json").write_text(json.dumps(
+            {"workload": "cfg2", "rows": 4, "n": 1024, "dtype": "f32", "calls": 2,
+             "variants": ["softmax2p", "softmax3p_recompute"], "ms_per_call": {}}) + "\n")
+
+    import json
+    run("rd", lambda k: {"TCC_EA0_RDREQ_sum": 10, "TCC_EA0_RDREQ_32B_sum": 2, "TCC_EA0_RDREQ_64B_sum": 3,
+                         "TCC_EA0_RDREQ_128B_sum": 5 if k == two else 50})
+    run("wr", lambda k: {"WRITE_SIZE": 16 if k == two else 0})
+    run("sq", lambda k: {"SQ_INSTS_VALU": 640 if k == two else 64, "SQ_WAVES": 64})
+    data = P.collect(str(tmp_path))
+    assert list(data) == ["cfg2"] and list(data["cfg2"]["variants"]) == ["softmax2p", "softmax3p_recompute"]
+    c = P.build_counters(data, "abc1234", str(tmp_path))
+    two_rec = c["workloads"]["cfg2"]["softmax2p"]
+    assert two_rec["fetch_bytes"] == 32 * 2 + 64 * 3 + 128 * 5 and two_rec["write_bytes"] == 16 * 1024
+    assert two_rec["hbm_bytes"] == two_rec["fetch_bytes"] + two_rec["write_bytes"]
+    k = two_rec["kernels"]["rows_2p"]
+    assert k["launches_per_call"] == 1.0 and k["valu_lane_ops_per_element"] == 640 * 64 / 4096
+    assert k["instantiation"] == "rows_2p<F32x4, 1024, 8>"
+    rec = c["workloads"]["cfg2"]["softmax3p_recompute"]
+    assert rec["fetch_bytes"] == 32 * 2 + 64 * 3 + 128 * 50 and rec["write_bytes"] == 0
+    assert c["_meta"]["commit"] == "abc1234"
+    assert P.short(two) == "rows_2p<F32x4, 1024, 8>" and P.base(mx) == "chunk_max"
