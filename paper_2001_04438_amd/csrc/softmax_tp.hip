@@ -63,13 +63,20 @@ static bool valid_unroll(int64_t u, int elem_bytes)
 // Rows path: the largest tile (block * unroll vectors per round) that wastes at
 // most 15 % of its last round on the row.
 constexpr int64_t kWaveRowMaxVecs = 256;  // rows up to this many vectors get a wave each ...
-constexpr int64_t kQuadRowMaxVecs = 64;   // ... and up to this many a row of 16 lanes (shape.block 16)
+constexpr int64_t kQuadRowMaxVecs = 64;   // ... up to this many a row of 16 lanes (shape.block 16) ...
 constexpr int kQuad = 16;
+constexpr int64_t kTinyRowMaxVecs = 16;   // ... and up to this many a quad of 4 lanes (shape.block 4)
+constexpr int kTiny = 4;
 
 static void rows_shape(const Tuning &g_tune, int64_t nvec, int elem_bytes, softmax_tp_shape_t *s)
 {
     s->chunk_vecs = 0;
     s->chunks = 1;
+    if (nvec <= kTinyRowMaxVecs && !g_tune.block_rows && !g_tune.unroll_rows) {
+        s->block = kTiny;  // four lanes per row, sixty-four rows per workgroup
+        s->unroll = nvec <= kTiny ? 1 : nvec <= 2 * kTiny ? 2 : 4;
+        return;
+    }
     if (nvec <= kQuadRowMaxVecs && !g_tune.block_rows && !g_tune.unroll_rows) {
         s->block = kQuad;  // sixteen lanes per row, sixteen rows per workgroup
         s->unroll = nvec <= kQuad ? 1 : nvec <= 2 * kQuad ? 2 : 4;
@@ -160,7 +167,8 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
         if (rows > kThreadsMax / p->rows.block)
             return TP_ERR_TOO_LARGE;
         p->launches = 1;
-        return (p->rows.block == kWave || p->rows.block == kQuad || valid_block(p->rows.block)) &&
+        return (p->rows.block == kWave || p->rows.block == kQuad || p->rows.block == kTiny ||
+                valid_block(p->rows.block)) &&
                        valid_unroll(p->rows.unroll, elem_bytes)
                    ? TP_OK : TP_ERR_TUNING;
     }
@@ -335,7 +343,8 @@ template <class IO>
 static int run_rows(Algo algo, const softmax_tp_plan_t &plan, const typename IO::elem *x,
                     typename IO::elem *y, int64_t rows, int64_t n, hipStream_t st)
 {
-    if (plan.rows.block == kWave || plan.rows.block == kQuad) {  // short rows: a lane group per row
+    if (plan.rows.block == kWave || plan.rows.block == kQuad || plan.rows.block == kTiny) {
+        // short rows: a lane group per row
         const int64_t per_group = kShortBlock / plan.rows.block;
         const dim3 wgrid((uint32_t)((rows + per_group - 1) / per_group));
         const dim3 wblock(kShortBlock);
@@ -349,9 +358,13 @@ static int run_rows(Algo algo, const softmax_tp_plan_t &plan, const typename IO:
         };
         if (plan.rows.block == kWave)
             return plan.rows.unroll == 2 ? go(ic<kWave>{}, ic<2>{}) : go(ic<kWave>{}, ic<4>{});
-        return plan.rows.unroll == 1   ? go(ic<kQuad>{}, ic<1>{})
-               : plan.rows.unroll == 2 ? go(ic<kQuad>{}, ic<2>{})
-                                       : go(ic<kQuad>{}, ic<4>{});
+        if (plan.rows.block == kQuad)
+            return plan.rows.unroll == 1   ? go(ic<kQuad>{}, ic<1>{})
+                   : plan.rows.unroll == 2 ? go(ic<kQuad>{}, ic<2>{})
+                                           : go(ic<kQuad>{}, ic<4>{});
+        return plan.rows.unroll == 1   ? go(ic<kTiny>{}, ic<1>{})
+               : plan.rows.unroll == 2 ? go(ic<kTiny>{}, ic<2>{})
+                                       : go(ic<kTiny>{}, ic<4>{});
     }
     const dim3 grid((uint32_t)rows);
     return with_shape<IO>(plan.rows, [&](auto B, auto U) {
@@ -620,7 +633,7 @@ static int run_onchip(int algo, const typename IO::elem *x, typename IO::elem *y
     if (hi <= kWaveRowMaxVecs) {  // short rows: a lane group per row, as on the rows path
         if (rows > kThreadsMax / kWave)
             return TP_ERR_TOO_LARGE;
-        const int lanes = hi <= kQuadRowMaxVecs ? kQuad : kWave;
+        const int lanes = hi <= kQuadRowMaxVecs ? kQuad : kWave;  // a lane holds at most one edge element
         const int64_t per_group = kShortBlock / lanes;
         const dim3 wgrid((uint32_t)((rows + per_group - 1) / per_group)), wblock(kShortBlock);
         auto go = [&](auto LANES, auto U) {

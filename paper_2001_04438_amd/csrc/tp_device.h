@@ -132,26 +132,41 @@ __device__ __forceinline__ void wave_pair(float &m, float &n)
     n = nw;
 }
 
-// The same reductions over LANES = 64 (the wave) or LANES = 16 (each row of 16 lanes on its own,
-// four independent results per wave: the DPP butterfly alone, no cross-row step).
+// The same reductions over a group of LANES lanes, every group of the wave on its own:
+// LANES = 64 (the wave), 16 (a DPP row: the four butterfly steps, no cross-row step) or 4 (a
+// quad: the first two steps).
 template <int LANES>
 __device__ __forceinline__ float lanes_max(float v)
 {
-    static_assert(LANES == 64 || LANES == 16, "a wave or a row of 16 lanes");
-    if constexpr (LANES == 64)
+    static_assert(LANES == 64 || LANES == 16 || LANES == 4, "a wave, a row of 16 lanes or a quad");
+    if constexpr (LANES == 64) {
         return wave_max(v);
-    TP_ROW_BUTTERFLY(v, op_max)
-    return v;
+    } else {
+        v = fmaxf(v, dpp<0xB1>(v));
+        v = fmaxf(v, dpp<0x4E>(v));
+        if constexpr (LANES == 16) {
+            v = fmaxf(v, dpp<0x141>(v));
+            v = fmaxf(v, dpp<0x140>(v));
+        }
+        return v;
+    }
 }
 
 template <int LANES>
 __device__ __forceinline__ float lanes_sum(float v)
 {
-    static_assert(LANES == 64 || LANES == 16, "a wave or a row of 16 lanes");
-    if constexpr (LANES == 64)
+    static_assert(LANES == 64 || LANES == 16 || LANES == 4, "a wave, a row of 16 lanes or a quad");
+    if constexpr (LANES == 64) {
         return wave_sum(v);
-    TP_ROW_BUTTERFLY(v, op_add)
-    return v;
+    } else {
+        v += dpp<0xB1>(v);
+        v += dpp<0x4E>(v);
+        if constexpr (LANES == 16) {
+            v += dpp<0x141>(v);
+            v += dpp<0x140>(v);
+        }
+        return v;
+    }
 }
 
 template <int LANES>
@@ -538,11 +553,10 @@ __device__ __forceinline__ void stream(const Seg<IO> &s, P &p, uint32_t tid = th
             }
         }
     }
-    if (s.edges) {
-        const int64_t ntail = s.n - s.tail0;
-        const int64_t nedge = s.head + ntail;
-        if ((int64_t)tid < nedge) {
-            const int64_t i = (int)tid < s.head ? (int64_t)tid : s.tail0 + ((int64_t)tid - s.head);
+    if (s.edges) {  // at most 2 (V - 1) elements: one round, except for lane groups of four
+        const int nedge = s.head + (int)(s.n - s.tail0);
+        for (int e = (int)tid; e < nedge; e += BLOCK) {
+            const int64_t i = e < s.head ? (int64_t)e : s.tail0 + (e - s.head);
             float f = IO::load1(s.xrow + i), o;
             p.template group<1>(&f, &o);
             if constexpr (P::kWrite)

@@ -77,6 +77,7 @@ __global__ __launch_bounds__(BLOCK) void rows_3p_reload(const typename IO::elem 
 // reduction.  LANES = 64: one wave per row, four rows per workgroup.  LANES = 16, for rows of
 // at most 64 vectors: one 16-lane DPP row per softmax row, sixteen rows per workgroup, so the
 // per-row cost of reductions and addressing is shared by four rows per wave instruction.
+// LANES = 4, for rows of at most 16 vectors: a quad per row, sixty-four rows per workgroup.
 
 constexpr int kShortBlock = 256;
 

@@ -202,23 +202,25 @@ def test_edge_lengths_bf16(gpu, oracle_mod):
 
 @pytest.mark.parametrize("name,tol", ALGOS_F32)
 def test_short_rows_one_lane_group_each(gpu, oracle_mod, name, tol):
-    """Rows of at most 64 vectors get 16 lanes each (16 rows per workgroup), up to 256 vectors a
-    wave each (4 rows per workgroup): every unroll of both, row counts that leave groups idle."""
+    """Rows of at most 16 vectors get a quad of lanes each (64 rows per workgroup), up to 64 vectors
+    16 lanes each (16 rows per workgroup), up to 256 vectors a wave each (4 rows per workgroup): every
+    unroll of each, row counts that leave groups idle."""
     rng = np.random.default_rng(83)
-    for rows, n, lanes in ((1001, 100, 16), (4097, 256, 16), (3000, 33, 16), (50, 1, 16), (17, 64, 16),
-                           (1, 129, 16), (33, 7, 16), (260, 255, 16),
+    for rows, n, lanes in ((1001, 100, 16), (4097, 256, 16), (3000, 33, 4), (50, 1, 4), (17, 64, 4),
+                           (1, 129, 16), (33, 7, 4), (260, 255, 16), (5000, 16, 4), (777, 61, 4), (65, 65, 16),
                            (6, 1024, 64), (513, 1021, 64), (1003, 257, 64), (5, 600, 64)):
         assert gpu.softmax_tp_plan(rows, n).rows.block == lanes
         x = rng.normal(0, 5, size=(rows, n)).astype(np.float32)
         _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
-    for n in (255, 1001):
+    for n in (50, 255, 1001):      # unaligned rows: up to six edge elements, more than a quad has lanes
         x = rng.normal(0, 5, size=(333, n)).astype(np.float32)
         _check(oracle_mod, x, _run(getattr(gpu, name), x, x_off=1, y_off=1), tol)
         _check(oracle_mod, x, _run(getattr(gpu, name), x, x_off=1, y_off=2), tol)   # element-wise format
         _check(oracle_mod, x, _run(getattr(gpu, name), x, inplace=True), tol)
     # rows far apart in magnitude side by side in one wave: the 16-lane reductions do not mix them
-    x = rng.normal(0, 2, size=(64, 200)).astype(np.float32) + (np.arange(64, dtype=np.float32) * 900 - 30000)[:, None]
-    _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
+    for n in (200, 40):           # 16 lanes per row, 4 lanes per row
+        x = rng.normal(0, 2, size=(64, n)).astype(np.float32) + (np.arange(64, dtype=np.float32) * 900 - 30000)[:, None]
+        _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
     x[5, 17] = np.nan
     y = _run(getattr(gpu, name), x)
     assert np.isnan(y[5]).all() and np.isfinite(np.delete(y, 5, axis=0)).all()
@@ -238,7 +240,7 @@ def test_short_rows_one_wave_each_bf16(gpu, oracle_mod):
     rng = np.random.default_rng(84)
     for name in ("softmax2p_bf16io", "softmax3p_recompute_bf16io", "softmax3p_reload_bf16io"):
         for rows, n in ((1001, 100), (4097, 512), (7, 2048), (513, 2041), (300, 513), (9, 8), (2000, 37)):
-            assert gpu.softmax_tp_plan(rows, n, 2).rows.block == (16 if n <= 512 else 64)
+            assert gpu.softmax_tp_plan(rows, n, 2).rows.block == (4 if n <= 128 else 16 if n <= 512 else 64)
             x = workloads.f32_to_bf16_bits(rng.normal(0, 5, size=(rows, n)).astype(np.float32)).reshape(rows, n)
             _check(oracle_mod, x, _run(getattr(gpu, name), x), TOL_BF16, bf16=True)
         x = workloads.cfg5(rows=77, n=1003)

@@ -128,12 +128,13 @@ def test_planner_covers_odd_shapes(B):
             V = (16 // s) if congruent else 1
             assert p.vector_elems == V
             if p.path == 1:
-                assert n * s <= 256 * 1024 and p.rows.block in (16, 64, 256, 512, 1024)
+                assert n * s <= 256 * 1024 and p.rows.block in (4, 16, 64, 256, 512, 1024)
                 nvec = -(-n // V)
-                assert (p.rows.block == 16) == (nvec <= 64)          # very short rows: 16 lanes each
+                assert (p.rows.block == 4) == (nvec <= 16)           # tiny rows: a quad of lanes each
+                assert (p.rows.block == 16) == (16 < nvec <= 64)     # very short rows: 16 lanes each
                 assert (p.rows.block == 64) == (64 < nvec <= 256)    # short rows: a wave each
-                if p.rows.block == 16:
-                    assert p.rows.unroll * 16 >= nvec and p.rows.unroll in (1, 2, 4)
+                if p.rows.block in (4, 16):
+                    assert p.rows.unroll * p.rows.block >= nvec and p.rows.unroll in (1, 2, 4)
             else:
                 nvec = -(-n // V)
                 for shape in (p.reduce, p.map, p.mapsum):
@@ -143,8 +144,8 @@ def test_planner_covers_odd_shapes(B):
     assert big.path == 2 and big.map.chunks * big.map.chunk_vecs >= (1 << 38)
     # a launch holds fewer than 2^32 threads: shapes beyond that are refused, not truncated
     assert big.map.chunks * big.map.block < 2 ** 32 and big.map.chunk_vecs > 2048
-    assert B.softmax_tp_plan(1 << 27, 64).rows.block == 16      # 2^31 threads: still one launch
-    for rows, n in ((1 << 23, 8192), (1, 1 << 60), (1 << 29, 64), (1 << 27, 300)):
+    assert B.softmax_tp_plan(1 << 29, 64).rows.block == 4       # 2^31 threads: still one launch
+    for rows, n in ((1 << 23, 8192), (1, 1 << 60), (1 << 31, 64), (1 << 27, 300)):
         with pytest.raises(B.SoftmaxTpError) as e:
             B.softmax_tp_plan(rows, n)
         assert e.value.code == B.TP_ERR_TOO_LARGE
