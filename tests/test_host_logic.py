@@ -339,3 +339,21 @@ def test_prof_summary_cuts_a_counter_file_into_variants(tmp_path, monkeypatch):
     assert rec["fetch_bytes"] == 32 * 2 + 64 * 3 + 128 * 50 and rec["write_bytes"] == 0
     assert c["_meta"]["commit"] == "abc1234"
     assert P.short(two) == "rows_2p<F32x4, 1024, 8>" and P.base(mx) == "chunk_max"
+
+
+def test_bench_line_never_prints_an_unlabelled_fraction_above_one():
+    """bench.describe_variant: with a counter record a cache-assisted variant is priced on the bytes
+    that reached memory; without one, a rate above the HBM peak is withheld and explained."""
+    sys.path.insert(0, ROOT)
+    import bench
+    alg = 3 * 1024 * 32768 * 4                       # Two-Pass on 1024 x 32768 fp32
+    copy_ms, copy_bytes = 0.046, 2 * 1024 * 32768 * 4
+    e = bench.describe_variant({}, alg, 0.045, copy_ms, copy_bytes, {"hbm_bytes": 260_000_000})
+    assert e["cache_assisted"] is True and e["hbm_bytes_measured"] == 260_000_000
+    assert e["GBps_algorithmic"] > bench.HBM_PEAK_GBS > e["GBps_effective"]
+    assert 0 < e["frac_of_hbm_peak"] <= 1 and e["frac_of_hbm_peak"] == pytest.approx(260e6 / 0.045 / 1e6 / 8000)
+    assert e["frac_of_stream_copy"] == pytest.approx((260e6 / 0.045) / (copy_bytes / copy_ms))
+    e = bench.describe_variant({}, alg, 0.045, copy_ms, copy_bytes, None)
+    assert e["cache_assisted"] is None and e["frac_of_hbm_peak"] is None and "frac_of_hbm_peak_note" in e
+    e = bench.describe_variant({}, alg, 0.060, copy_ms, copy_bytes, {"hbm_bytes": alg})
+    assert e["cache_assisted"] is False and e["frac_of_hbm_peak"] == pytest.approx(alg / 0.060 / 1e6 / 8000)
