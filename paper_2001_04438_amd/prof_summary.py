@@ -73,6 +73,12 @@ def base(name: str) -> str:
     return short(name).split("<")[0]
 
 
+def newest(pattern):
+    """Files matching the pattern, most recently written first (a directory that several profiler
+    runs wrote into holds one file per run, named after the process)."""
+    return sorted(glob.glob(pattern, recursive=True), key=os.path.getmtime, reverse=True)
+
+
 def read_run(root, workload, kind):
     """-> (info from the run's JSON line, dispatch list in launch order).  A dispatch is
     {"kernel", "grid", "block", "us", counters...}; None if the run is missing."""
@@ -87,8 +93,8 @@ def read_run(root, workload, kind):
             info = json.loads(line)
     if info is None:
         return None
-    files = glob.glob(os.path.join(d, "**", "*_counter_collection.csv"), recursive=True) or \
-        glob.glob(os.path.join(d, "**", "*_kernel_trace.csv"), recursive=True)
+    files = newest(os.path.join(d, "**", "*_counter_collection.csv")) or \
+        newest(os.path.join(d, "**", "*_kernel_trace.csv"))
     if not files:
         return None
     disp = collections.OrderedDict()
@@ -394,7 +400,7 @@ def write_dominant_md(data, counters, path):
 
 def write_bench_trace_md(root, path):
     """Kernel durations of the default `bench.py` run under rocprofv3 --kernel-trace --stats (DIR/bench.trace)."""
-    files = glob.glob(os.path.join(root, "bench.trace", "**", "*_kernel_trace.csv"), recursive=True)
+    files = newest(os.path.join(root, "bench.trace", "**", "*_kernel_trace.csv"))
     line = os.path.join(root, "bench.trace.json")
     if not files or not os.path.exists(line):
         return False
