@@ -247,14 +247,17 @@ def test_integer_exponent_evaluator_on_the_host(tmp_path):
     rounded sum, one-constant reduction), swept the same way: n from the bits equals
     z - 1.5 * 2^23 and round(x log2 e) everywhere up to |x| = 2.9e6; against what it approximates by
     design, e^(x - n fl(ln 2)) 2^n, it is as accurate as Algorithm 4 (< 2 ULP); against e^x itself
-    the one-constant reduction costs |n| * 1.9e-9, i.e. < 5.5 ULP where fp32 exp is finite."""
+    the one-constant reduction costs |n| * 1.9e-9, i.e. < 5.5 ULP where fp32 exp is finite.  Every 9th
+    input by default, every input with TP_EXHAUSTIVE=1 (two minutes on 8 cores; last full run:
+    2,237,668,968 inputs, 1.745 ULP and 5.053 ULP, no exception in n)."""
     exe = tmp_path / "sweep"
     subprocess.run(["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-mfma", "-o", str(exe),
                     os.path.join(ROOT, "tests", "host_extexp_sweep.c"), "-lm", "-lpthread"], check=True)
     threads = str(min(16, os.cpu_count() or 1))
-    out = subprocess.run([str(exe), "-104", "89", "9", threads, "2", "1"], check=True,
+    stride = "1" if os.environ.get("TP_EXHAUSTIVE") == "1" else "9"
+    out = subprocess.run([str(exe), "-104", "89", stride, threads, "2", "1"], check=True,
                          capture_output=True, text=True).stdout.split()
-    assert int(out[0]) > 2.2e9 / 9 * 0.99
+    assert int(out[0]) > 2.2e9 / int(stride) * 0.99
     assert float(out[1]) < 2.0 and int(out[4]) == 0, out
     assert 2.0 < float(out[6]) < 5.5, out           # the dropped term is visible, and bounded
     assert math.sqrt(2) / 2 * (1 - 1e-5) <= float(out[2]) and float(out[3]) <= math.sqrt(2) * (1 + 1e-5)
