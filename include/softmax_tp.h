@@ -20,8 +20,12 @@
  *            stream has finished.
  *   inputs   finite values.  Full accuracy (max relative error 4e-6 for fp32
  *            I/O) holds for |x| <= 1e5; see the Two-Pass entry for larger
- *            magnitudes.  A NaN anywhere in a row makes that row's outputs NaN;
- *            infinities are not supported.
+ *            magnitudes.  A NaN anywhere in a row makes that row's outputs NaN, and
+ *            so does an infinity of either sign (the range reduction turns it into
+ *            NaN); other rows are not affected.  To mask an element out, give it a
+ *            large finite negative value, not -inf.  The 16-bit entry points take the
+ *            exponent from the bit pattern of x log2(e) + 1.5 * 2^23, which is valid
+ *            for |x| < 2.9e6: every binary16 value, and bfloat16 values up to there.
  *   return   0 on success; a negative TP_ERR_* code for an invalid argument,
  *            detected before any GPU call is made; a positive value is the
  *            hipError_t of a failed allocation or launch.
