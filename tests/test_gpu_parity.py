@@ -482,6 +482,20 @@ def test_extreme_magnitudes_two_pass(gpu, oracle_mod):
     _check(oracle_mod, xb, _run(gpu.softmax2p_bf16io, xb), TOL_BF16, bf16=True)
 
 
+def test_bf16_up_to_the_edge_of_its_exponent_trick(gpu, oracle_mod):
+    """The 16-bit entry points read the exponent from the bit pattern of x log2e + 1.5 * 2^23, valid
+    for |x| < 2.9e6.  bf16 values of that size are 8192 or 16384 apart, so rows there are ties at the
+    maximum sharing the mass; rows a few thousand in size still have structure."""
+    rng = np.random.default_rng(86)
+    for centre, spread in ((2.0e6, 3e4), (-2.7e6, 5e4), (3.0e4, 40.0), (-1.0e5, 300.0)):
+        x = (rng.normal(0, spread, size=(7, 3001)) + centre).astype(np.float32)
+        xb = workloads.f32_to_bf16_bits(x).reshape(x.shape)
+        for name in ("softmax2p_bf16io", "softmax2p_onchip_bf16io", "softmax3p_recompute_bf16io"):
+            y = _run(getattr(gpu, name), xb)
+            c = _check(oracle_mod, xb, y, TOL_BF16, bf16=True)
+            assert c.n_normal >= 7            # at least the maximum of every row
+
+
 def test_shift_invariance_on_gpu(gpu):
     rng = np.random.default_rng(81)
     x = (rng.integers(-3000, 3000, size=(4, 777)) / 256.0).astype(np.float32)
