@@ -245,15 +245,38 @@ def write_kernels_md(data, counters, root, path):
              "Durations are from the kernel trace (not from the counter runs, which serialise dispatches); the "
              "first few dozen launches after the host has kept the device idle run at a reduced shader clock "
              "(1.5 to 2.0 instead of 2.4 GHz, which slows the passes with arithmetic in them by up to a quarter), "
-             "hence 400 calls per variant and the median next to the average.\n")
+             "hence 400 calls per variant and the median next to the average.  The last two columns are the "
+             "per-pass bandwidth picture (the analogue of the paper's per-pass charts against STREAM, Section "
+             "6.4): the bytes this kernel moved between L2 and the fabric over its median duration, and that "
+             "rate over the rate of the calibration kernel of the same workload with the same kind of traffic "
+             "(`chunk_read` for a pass that only reads, `chunk_copy` for one that also writes).\n")
     for w, wl in data.items():
         info = wl["info"]
         s = ELEM_BYTES[info["dtype"]]
         elems = info["rows"] * info["n"]
         L.append(f"## {w}: {info['rows']} x {info['n']} {info['dtype']} ({elems * s / 2**20:,.1f} MiB in, the same out)\n")
         L.append("| variant | kernel | launches per call | grid x block | avg us | median | min | max | MiB read | "
-                 "MiB written | VALU lane-ops per element |")
-        L.append("|---|---|---|---|---|---|---|---|---|---|---|")
+                 "MiB written | VALU lane-ops per element | GB/s on those bytes (median) | of the calibration kernel |")
+        L.append("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+
+        def moved(variant, kname):
+            """(bytes between L2 and fabric, median us) of one kernel, or None."""
+            kinds = wl.get("variants", {}).get(variant, {})
+            rd, wr, tr = (kinds.get(k, {}).get(kname) for k in ("rd", "wr", "trace"))
+            if not (rd and wr and tr):
+                return None
+            return read_bytes(rd) + wr.get("WRITE_SIZE", 0) * 1024, tr["us_med"], wr.get("WRITE_SIZE", 0) * 1024
+
+        # the calibration kernels of the same workload: a pass that only reads is set against the
+        # read kernel, one that reads and writes against the copy kernel (Section 6.4 does the same
+        # with STREAM)
+        calib = {}
+        for cv in ("read", "copy"):
+            for kname in wl.get("variants", {}).get(cv, {}).get("trace", {}):
+                if base(kname) in ("chunk_read", "chunk_copy"):
+                    m = moved(cv, kname)
+                    if m:
+                        calib[cv] = m[0] / m[1]
         for variant, kinds in wl.get("variants", {}).items():
             ref = kinds.get("trace") or kinds.get("rd") or kinds.get("sq") or {}
             for kname, t in ref.items():
@@ -261,13 +284,21 @@ def write_kernels_md(data, counters, root, path):
                 wr = kinds.get("wr", {}).get(kname)
                 sq = kinds.get("sq", {}).get(kname)
                 tr = kinds.get("trace", {}).get(kname)
-                L.append("| {} | `{}` | {:g} | {} x {} | {} | {} | {} | {} | {} | {} | {} |".format(
+                m = moved(variant, kname)
+                rate = against = "-"
+                if m and m[0] > 2**20:
+                    rate = f"{m[0] / m[1] / 1e3:,.0f}"
+                    kind = "copy" if m[2] > 2**20 else "read"
+                    if kind in calib:
+                        against = f"{m[0] / m[1] / calib[kind]:.2f} of {kind}"
+                L.append("| {} | `{}` | {:g} | {} x {} | {} | {} | {} | {} | {} | {} | {} | {} | {} |".format(
                     variant, kname, t["launches_per_call"], t["grid_threads"] // max(t["block"], 1), t["block"],
                     f"{tr['us_avg']:.1f}" if tr else "-", f"{tr['us_med']:.1f}" if tr else "-",
                     f"{tr['us_min']:.1f}" if tr else "-", f"{tr['us_max']:.1f}" if tr else "-",
                     f"{read_bytes(rd) / 2**20:,.2f}" if rd else "-",
                     f"{wr.get('WRITE_SIZE', 0) / 1024:,.2f}" if wr else "-",
-                    f"{sq['SQ_INSTS_VALU'] * 64 / elems:.1f}" if sq and "SQ_INSTS_VALU" in sq else "-"))
+                    f"{sq['SQ_INSTS_VALU'] * 64 / elems:.1f}" if sq and "SQ_INSTS_VALU" in sq else "-",
+                    rate, against))
         L.append("")
         L.append("| variant | algorithmic MiB per call (Table 2) | measured MiB per call | measured / algorithmic | |")
         L.append("|---|---|---|---|---|")
