@@ -230,7 +230,9 @@ typedef struct {
                               kernel of its own then merges; 0 if the next pass folds them itself */
     int32_t nt_first_load; /* path 2: 1 if even the first read of x carries the non-temporal hint
                               (input too large for any cache to help the second read) */
-    softmax_tp_shape_t rows;    /* path 1 */
+    softmax_tp_shape_t rows;    /* path 1, Two-Pass */
+    softmax_tp_shape_t rows_recompute; /* path 1, Three-Pass with recomputation */
+    softmax_tp_shape_t rows_reload;    /* path 1, Three-Pass with reloading */
     softmax_tp_shape_t reduce;  /* path 2, read-only passes (Two-Pass pass 1; max; sum-exp) */
     softmax_tp_shape_t map;     /* path 2, read-write passes (Two-Pass pass 2; exp-scale; scale) */
     softmax_tp_shape_t mapsum;  /* path 2, the read-write pass that also reduces (exp-store) */

@@ -75,6 +75,8 @@ class Plan(ctypes.Structure):
         ("merge_kernel", ctypes.c_int32),
         ("nt_first_load", ctypes.c_int32),
         ("rows", Shape),
+        ("rows_recompute", Shape),
+        ("rows_reload", Shape),
         ("reduce", Shape),
         ("map", Shape),
         ("mapsum", Shape),
@@ -90,7 +92,8 @@ class Plan(ctypes.Structure):
             for k in ("reduce", "map", "mapsum"):
                 d.pop(k)
         else:
-            d.pop("rows")
+            for k in ("rows", "rows_recompute", "rows_reload"):
+                d.pop(k)
         return d
 
 

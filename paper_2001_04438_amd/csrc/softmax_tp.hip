@@ -68,7 +68,33 @@ constexpr int kQuad = 16;
 constexpr int64_t kTinyRowMaxVecs = 16;   // ... and up to this many a quad of 4 lanes (shape.block 4)
 constexpr int kTiny = 4;
 
-static void rows_shape(const Tuning &g_tune, int64_t nvec, int elem_bytes, softmax_tp_shape_t *s)
+// Workgroup size and loads in flight on the rows path, by row length in 16-byte vectors.  From
+// round-robin sweeps of every shape over rows of 1.5 K to 128 K elements: a lane should see two
+// to eight vectors (a single round leaves nothing to overlap the loads with, many rounds of a
+// small workgroup leave the row-wide reductions to too few waves), the variant that stores and
+// re-reads its exponentials wants the larger workgroup one step earlier, and the 16-bit formats,
+// with twice the arithmetic per vector, keep fewer loads in flight.
+struct RowStep {
+    int64_t below;  // applies to rows shorter than this many vectors
+    int block, unroll;
+};
+constexpr int64_t kAnyLength = INT64_MAX;
+static const RowStep kRowSteps[2][3][5] = {
+    {   // fp32
+        {{1024, 256, 2}, {3072, 512, 2}, {8192, 1024, 4}, {kAnyLength, 1024, 8}, {kAnyLength, 1024, 8}},
+        {{1024, 256, 2}, {3072, 512, 2}, {6144, 1024, 4}, {kAnyLength, 1024, 8}, {kAnyLength, 1024, 8}},
+        {{768, 256, 2}, {1536, 512, 2}, {3072, 1024, 2}, {4096, 1024, 4}, {kAnyLength, 1024, 8}},
+    },
+    {   // bf16, fp16
+        {{1536, 256, 2}, {4096, 512, 2}, {12288, 1024, 2}, {kAnyLength, 1024, 4}, {kAnyLength, 1024, 4}},
+        {{1536, 256, 2}, {2560, 512, 2}, {8192, 512, 4}, {kAnyLength, 1024, 4}, {kAnyLength, 1024, 4}},
+        {{768, 256, 2}, {1536, 512, 2}, {6144, 1024, 2}, {kAnyLength, 1024, 4}, {kAnyLength, 1024, 4}},
+    },
+};
+
+// algo: 0 Two-Pass, 1 Three-Pass with recomputation, 2 Three-Pass with reloading
+static void rows_shape(const Tuning &g_tune, int64_t nvec, int elem_bytes, int algo,
+                       softmax_tp_shape_t *s)
 {
     s->chunk_vecs = 0;
     s->chunks = 1;
@@ -87,17 +113,10 @@ static void rows_shape(const Tuning &g_tune, int64_t nvec, int elem_bytes, softm
         s->unroll = nvec <= 2 * kWave ? 2 : 4;
         return;
     }
-    static const int cand_f32[][2] = {{1024, 8}, {1024, 4}, {512, 4}, {512, 2}, {256, 2}};
-    static const int cand_16bit[][2] = {{1024, 4}, {1024, 2}, {512, 2}, {256, 2}, {256, 2}};
-    const int(*cand)[2] = elem_bytes == 4 ? cand_f32 : cand_16bit;
-    s->block = cand[4][0];
-    s->unroll = cand[4][1];
-    for (int i = 0; i < 5; ++i) {
-        const int64_t tile = (int64_t)cand[i][0] * cand[i][1];
-        const int64_t padded = (nvec + tile - 1) / tile * tile;
-        if ((padded - nvec) * 100 <= nvec * 15) {
-            s->block = cand[i][0];
-            s->unroll = cand[i][1];
+    for (const RowStep &step : kRowSteps[elem_bytes == 4 ? 0 : 1][algo]) {
+        if (nvec < step.below) {
+            s->block = step.block;
+            s->unroll = step.unroll;
             break;
         }
     }
@@ -162,15 +181,20 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
         if (rows > kGridMax || nvec > kChunkVecsMax)
             return TP_ERR_TOO_LARGE;
         p->path = 1;
-        rows_shape(g_tune, nvec, elem_bytes, &p->rows);
-        // rows.block threads per row, whether that is a workgroup, a wave or a row of 16 lanes
-        if (rows > kThreadsMax / p->rows.block)
-            return TP_ERR_TOO_LARGE;
+        rows_shape(g_tune, nvec, elem_bytes, 0, &p->rows);
+        rows_shape(g_tune, nvec, elem_bytes, 1, &p->rows_recompute);
+        rows_shape(g_tune, nvec, elem_bytes, 2, &p->rows_reload);
         p->launches = 1;
-        return (p->rows.block == kWave || p->rows.block == kQuad || p->rows.block == kTiny ||
-                valid_block(p->rows.block)) &&
-                       valid_unroll(p->rows.unroll, elem_bytes)
-                   ? TP_OK : TP_ERR_TUNING;
+        for (const softmax_tp_shape_t *sh : {&p->rows, &p->rows_recompute, &p->rows_reload}) {
+            // block threads per row, whether that is a workgroup, a wave or a few lanes
+            if (rows > kThreadsMax / sh->block)
+                return TP_ERR_TOO_LARGE;
+            if (!((sh->block == kWave || sh->block == kQuad || sh->block == kTiny ||
+                   valid_block(sh->block)) &&
+                  valid_unroll(sh->unroll, elem_bytes)))
+                return TP_ERR_TUNING;
+        }
+        return TP_OK;
     }
 
     p->path = 2;
@@ -343,9 +367,12 @@ template <class IO>
 static int run_rows(Algo algo, const softmax_tp_plan_t &plan, const typename IO::elem *x,
                     typename IO::elem *y, int64_t rows, int64_t n, hipStream_t st)
 {
-    if (plan.rows.block == kWave || plan.rows.block == kQuad || plan.rows.block == kTiny) {
+    const softmax_tp_shape_t &shape = algo == kTwoPass     ? plan.rows
+                                      : algo == kRecompute ? plan.rows_recompute
+                                                           : plan.rows_reload;
+    if (shape.block == kWave || shape.block == kQuad || shape.block == kTiny) {
         // short rows: a lane group per row
-        const int64_t per_group = kShortBlock / plan.rows.block;
+        const int64_t per_group = kShortBlock / shape.block;
         const dim3 wgrid((uint32_t)((rows + per_group - 1) / per_group));
         const dim3 wblock(kShortBlock);
         auto go = [&](auto LANES, auto U) {
@@ -356,18 +383,18 @@ static int run_rows(Algo algo, const softmax_tp_plan_t &plan, const typename IO:
                 return launch(waves_3p_recompute<IO, L, TP_U>, wgrid, wblock, st, x, y, n, rows);
             return launch(waves_3p_reload<IO, L, TP_U>, wgrid, wblock, st, x, y, n, rows);
         };
-        if (plan.rows.block == kWave)
-            return plan.rows.unroll == 2 ? go(ic<kWave>{}, ic<2>{}) : go(ic<kWave>{}, ic<4>{});
-        if (plan.rows.block == kQuad)
-            return plan.rows.unroll == 1   ? go(ic<kQuad>{}, ic<1>{})
-                   : plan.rows.unroll == 2 ? go(ic<kQuad>{}, ic<2>{})
-                                           : go(ic<kQuad>{}, ic<4>{});
-        return plan.rows.unroll == 1   ? go(ic<kTiny>{}, ic<1>{})
-               : plan.rows.unroll == 2 ? go(ic<kTiny>{}, ic<2>{})
-                                       : go(ic<kTiny>{}, ic<4>{});
+        if (shape.block == kWave)
+            return shape.unroll == 2 ? go(ic<kWave>{}, ic<2>{}) : go(ic<kWave>{}, ic<4>{});
+        if (shape.block == kQuad)
+            return shape.unroll == 1   ? go(ic<kQuad>{}, ic<1>{})
+                   : shape.unroll == 2 ? go(ic<kQuad>{}, ic<2>{})
+                                       : go(ic<kQuad>{}, ic<4>{});
+        return shape.unroll == 1   ? go(ic<kTiny>{}, ic<1>{})
+               : shape.unroll == 2 ? go(ic<kTiny>{}, ic<2>{})
+                                   : go(ic<kTiny>{}, ic<4>{});
     }
     const dim3 grid((uint32_t)rows);
-    return with_shape<IO>(plan.rows, [&](auto B, auto U) {
+    return with_shape<IO>(shape, [&](auto B, auto U) {
         if (algo == kTwoPass)
             return launch(rows_2p<IO, TP_B, TP_U>, grid, dim3(TP_B), st, x, y, n);
         if (algo == kRecompute)

@@ -625,6 +625,34 @@ def test_launch_shapes(gpu, oracle_mod):
         gpu.softmax_tp_tune_reset()
 
 
+def test_every_default_shape_of_the_rows_path(gpu, oracle_mod):
+    """The planner gives every algorithm its own workgroup shape by row length; one row length inside
+    every step of every table, each algorithm in each format, all of them ragged."""
+    seen = set()
+    rng = np.random.default_rng(97)
+    for s, lengths in ((4, (2901, 3503, 5001, 9003, 14001, 19999, 30001, 50003)),
+                       (2, (5001, 9003, 15001, 24999, 40001, 59999, 90001, 120003))):
+        for n in lengths:
+            rows = 37
+            x = (rng.normal(0, 6, size=(rows, n)) + rng.uniform(-30, 30, size=(rows, 1))).astype(np.float32)
+            plan = gpu.softmax_tp_plan(rows, n, s)
+            assert plan.path == 1
+            for sh in (plan.rows, plan.rows_recompute, plan.rows_reload):
+                seen.add((s, sh.block, sh.unroll))
+            if s == 4:
+                for name, tol in ALGOS_F32:
+                    _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
+            else:
+                xb = workloads.f32_to_bf16_bits(x).reshape(x.shape)
+                xh = workloads.f32_to_f16_bits(x).reshape(x.shape)
+                for name in ("softmax2p_bf16io", "softmax3p_recompute_bf16io", "softmax3p_reload_bf16io"):
+                    _check(oracle_mod, xb, _run(getattr(gpu, name), xb), TOL_BF16, bf16=True)
+                for name, tol in ALGOS_F16:
+                    _check(oracle_mod, xh, _run(getattr(gpu, name), xh), tol, f16=True)
+    assert {(4, 256, 2), (4, 512, 2), (4, 1024, 2), (4, 1024, 4), (4, 1024, 8),
+            (2, 256, 2), (2, 512, 2), (2, 512, 4), (2, 1024, 2), (2, 1024, 4)} <= seen, seen
+
+
 @pytest.mark.parametrize("name,tol", ALGOS_F32)
 def test_partials_folded_by_the_consuming_pass(gpu, oracle_mod, name, tol):
     """65..128 partials per row: lanes fold two each; the fold_max key moves the hand-over

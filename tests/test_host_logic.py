@@ -84,6 +84,10 @@ def test_planner_on_the_benchmark_configurations(B):
     assert plans[3].merge_kernel == 1 and plans[3].reduce.chunks > 128
     assert plans[1].rows.block == 1024                      # config 2: one workgroup per row
     assert plans[4].vector_elems == 8 and plans[4].rows.unroll <= 4
+    # every algorithm has its own shape on the rows path: config 5, 2731 vectors per row
+    assert (plans[4].rows.block, plans[4].rows.unroll) == (512, 2)
+    assert (plans[4].rows_recompute.block, plans[4].rows_recompute.unroll) == (512, 4)
+    assert (plans[4].rows_reload.block, plans[4].rows_reload.unroll) == (1024, 2)
     assert plans[3].nt_first_load == 1 and plans[2].nt_first_load == 0
     # read-only passes: two workgroups of 256 threads per CU; read-write passes: one round each
     assert (plans[3].reduce.block, plans[3].reduce.unroll, plans[3].reduce.chunks) == (256, 4, 512)
@@ -135,6 +139,17 @@ def test_planner_covers_odd_shapes(B):
                 assert (p.rows.block == 64) == (64 < nvec <= 256)    # short rows: a wave each
                 if p.rows.block in (4, 16):
                     assert p.rows.unroll * p.rows.block >= nvec and p.rows.unroll in (1, 2, 4)
+                for other in (p.rows_recompute, p.rows_reload):
+                    # the lane-group shapes are shared; workgroup shapes may differ per algorithm
+                    assert (other.block < 256) == (p.rows.block < 256)
+                    if p.rows.block < 256:
+                        assert (other.block, other.unroll) == (p.rows.block, p.rows.unroll)
+                    else:
+                        assert other.block in (256, 512, 1024) and other.unroll in ((2, 4, 8) if s == 4 else (2, 4))
+                    assert other.chunks == 1 and other.chunk_vecs == 0
+                if p.rows.block >= 256:
+                    # a lane sees at least one and at most 32 rounds of loads (element-wise 16-bit rows)
+                    assert 1 <= -(-nvec // (p.rows.block * p.rows.unroll)) <= 32
             else:
                 nvec = -(-n // V)
                 for shape in (p.reduce, p.map, p.mapsum):
