@@ -46,6 +46,10 @@ constexpr int64_t kSmallRowBytes = 128 * 1024;     // ... unless the rows are th
 // the limit is low: 128 still beat a merge launch (1.3 %), 512 lost 10 % on the 1 GiB vector.
 constexpr int kFoldMax = 128;
 constexpr int64_t kLatencyBoundBytes = (int64_t)4 << 20;  // below this a launch costs more than its traffic
+// up to these sizes [fp32, 16-bit] a single row is cut into at most kFoldMax chunks for the
+// read-only passes, handled by 512 threads each up to the second size and by 1024 beyond
+constexpr int64_t kFewChunksBytes[2] = {(int64_t)64 << 20, (int64_t)32 << 20};
+constexpr int64_t kFewChunksMidBytes[2] = {(int64_t)16 << 20, (int64_t)4 << 20};
 constexpr int64_t kTargetReduce = 512;             // workgroups of a read-only pass (2 per CU)
 constexpr int64_t kNtFirstBytes = (int64_t)512 << 20;  // inputs beyond this outlive every cache
 // A launch may hold at most 2^32 - 1 threads in all (and 2^31 - 1 workgroups); grids are
@@ -204,16 +208,22 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
     // queues only add contention at the memory channels.
     {
         // (16-bit elements: twice the waves, these passes being bound by arithmetic there)
-        const int block = g_tune.block_reduce ? (int)g_tune.block_reduce
-                                              : (elem_bytes == 2 ? 512 : 256);
+        int block = elem_bytes == 2 ? 512 : 256;
         const int unroll = g_tune.unroll_reduce ? (int)g_tune.unroll_reduce : 4;
         const int64_t target = g_tune.target_reduce ? g_tune.target_reduce : kTargetReduce;
         int64_t per_row = (target + rows - 1) / rows;
         if (per_row < 1) per_row = 1;
-        // short inputs are bound by launch latency: stay within what the next pass folds by
-        // itself, which saves the merge launch
-        if (rows * row_bytes <= kLatencyBoundBytes && per_row > fold_limit && !g_tune.target_reduce)
+        // Up to a few dozen MiB a launch costs a good part of what its traffic does: stay within
+        // what the next pass folds by itself, which saves the merge launch, and make up for the
+        // fewer workgroups with larger ones (one to three rows only: more rows have at most
+        // fold_limit chunks each anyway).
+        const int64_t bytes = rows * row_bytes;
+        if (per_row > fold_limit && !g_tune.target_reduce && bytes <= kFewChunksBytes[elem_bytes == 2]) {
             per_row = fold_limit;
+            if (bytes > kLatencyBoundBytes)
+                block = bytes <= kFewChunksMidBytes[elem_bytes == 2] ? 512 : 1024;
+        }
+        if (g_tune.block_reduce) block = (int)g_tune.block_reduce;
         int rc = chunk_shape(rows, nvec, block, unroll, (nvec + per_row - 1) / per_row, &p->reduce);
         if (rc != TP_OK) return rc;
     }

@@ -143,9 +143,19 @@ def test_cfg4_single_long_vector(gpu, oracle_mod, name, tol):
     n = (1 << 23) + 3  # thousands of chunks, ragged tail
     x = workloads.cfg4(n=n)
     plan = gpu.softmax_tp_plan(1, n)
-    assert plan.path == 2 and plan.merge_kernel == 1 and plan.map.chunks >= 1024
+    # 32 MiB: 128 chunks of 1024 threads for the read-only passes, no merge launch
+    assert plan.path == 2 and plan.merge_kernel == 0 and plan.map.chunks >= 1024
+    assert plan.reduce.block == 1024 and 64 < plan.reduce.chunks <= 128
     c = _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
     assert c.n_normal < x.size // 100  # almost everything underflows next to the outliers
+    try:
+        # the arrangement of vectors beyond 64 MiB: 512 chunks and a merge launch
+        gpu.softmax_tp_tune("target_reduce", 512)
+        plan = gpu.softmax_tp_plan(1, n)
+        assert plan.merge_kernel == 1 and plan.reduce.block == 256 and plan.reduce.chunks > 128
+        _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
+    finally:
+        gpu.softmax_tp_tune_reset()
 
 
 def test_cfg5_bf16(gpu, oracle_mod):
@@ -666,14 +676,17 @@ def test_partials_folded_by_the_consuming_pass(gpu, oracle_mod, name, tol):
         _check(oracle_mod, x, want, tol)
         try:
             gpu.softmax_tp_tune("fold_max", 64)
+            assert gpu.softmax_tp_plan(rows, n).reduce.chunks <= 64   # inputs this short follow the limit
+            gpu.softmax_tp_tune("target_reduce", 512)                  # ... unless the sweep insists
             assert gpu.softmax_tp_plan(rows, n).merge_kernel == 1
             _check(oracle_mod, x, _run(fn, x), tol)
             gpu.softmax_tp_tune("fold_max", 512)
             x1 = workloads.cfg3(rows=1, n=3_000_017)
-            assert gpu.softmax_tp_plan(1, 3_000_017).merge_kernel == 0
+            plan = gpu.softmax_tp_plan(1, 3_000_017)
+            assert plan.merge_kernel == 0 and plan.reduce.chunks > 128
             _check(oracle_mod, x1, _run(fn, x1), tol)
         finally:
-            gpu.softmax_tp_tune("fold_max", 0)
+            gpu.softmax_tp_tune_reset()
 
 
 def test_bitwise_reproducible(gpu):

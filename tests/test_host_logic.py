@@ -107,12 +107,23 @@ def test_planner_on_the_benchmark_configurations(B):
 
 
 def test_planner_avoids_the_merge_launch_on_short_inputs(B):
-    # up to 4 MiB a launch costs more than its traffic: at most 128 chunks, folded by the next pass
-    for n in (1 << 16, 1 << 18, 1 << 20):
+    # up to 64 MiB (16-bit: 32 MiB) a launch costs a good part of what its traffic does: at most 128
+    # chunks, folded by the next pass, and larger workgroups to make up for their number
+    for n, block in ((1 << 16, 256), (1 << 18, 256), (1 << 20, 256), ((1 << 20) + 1, 512), (1 << 22, 512),
+                     ((1 << 22) + 1, 1024), (1 << 24, 1024)):
         p = B.softmax_tp_plan(1, n)
         assert p.path == 2 and p.reduce.chunks <= 128 and p.merge_kernel == 0 and p.launches == 2
-    p = B.softmax_tp_plan(1, (1 << 20) + 1)
-    assert p.reduce.chunks > 128 and p.merge_kernel == 1 and p.launches == 3
+        assert p.reduce.block == block and p.reduce.chunks * p.reduce.chunk_vecs * 4 >= n
+    for n, block in ((1 << 21, 512), ((1 << 21) + 8, 1024), (1 << 24, 1024)):
+        p = B.softmax_tp_plan(1, n, 2)
+        assert p.reduce.chunks <= 128 and p.merge_kernel == 0 and p.reduce.block == block
+    for n, s in (((1 << 24) + 1, 4), ((1 << 24) + 8, 2)):
+        p = B.softmax_tp_plan(1, n, s)
+        assert p.reduce.chunks > 128 and p.merge_kernel == 1 and p.launches == 3
+        assert p.reduce.block == (256 if s == 4 else 512)
+    B.softmax_tp_tune("block_reduce", 256)                      # an override still wins
+    assert B.softmax_tp_plan(1, 1 << 23).reduce.block == 256
+    B.softmax_tp_tune("block_reduce", 0)
     p = B.softmax_tp_plan(4, 1 << 24)
     assert p.reduce.chunks == 128 and p.merge_kernel == 0      # 512 workgroups over four rows
     B.softmax_tp_tune("fold_max", 64)

@@ -44,12 +44,13 @@ def _pair(gpu, x):
 
 # first call, then a smaller second call that reuses the front of the same scratch array
 CASES = [
-    # 512 partials + merge launch, then 8 rows of 64 partials folded by pass 2 itself
-    ((1, (1 << 23) + 3), (8, 300_001)),
+    # several hundred partials + merge launch, then 8 rows of 64 partials folded by pass 2 itself
+    ((1, 17_000_003), (8, 300_001)),
     # 64 rows x 8 partials, then one row whose partials land on the slots of rows 0..7
     ((64, 200_003), (1, 1_000_001)),
-    # merge launch both times, fewer chunks the second time (stale partials behind the live ones)
-    ((2, 6_000_001), (1, 2_000_003)),
+    # merge launch over two rows, then one row of 128 partials that pass 2 folds itself (stale
+    # partials and a stale merged pair behind the live ones)
+    ((2, 9_000_001), (1, (1 << 23) + 3)),
     # rows path (no scratch), then chunk path
     ((300, 5000), (3, 70_001)),
 ]
@@ -57,6 +58,8 @@ CASES = [
 
 @pytest.mark.parametrize("first,second", CASES)
 def test_static_scratch_matches_the_allocating_entry_point(gpu, oracle_mod, first, second):
+    if first[1] > 8_000_000:
+        assert gpu.softmax_tp_plan(*first).merge_kernel == 1 and gpu.softmax_tp_plan(*second).merge_kernel == 0
     for rows, n in (first, second):
         x = workloads.cfg3(rows=rows, n=n)
         print(f"softmax2p_f32_static {rows} x {n}", flush=True)
