@@ -386,3 +386,11 @@ def test_bench_line_never_prints_an_unlabelled_fraction_above_one():
     assert e["cache_assisted"] is None and e["frac_of_hbm_peak"] is None and "frac_of_hbm_peak_note" in e
     e = bench.describe_variant({}, alg, 0.060, copy_ms, copy_bytes, {"hbm_bytes": alg})
     assert e["cache_assisted"] is False and e["frac_of_hbm_peak"] == pytest.approx(alg / 0.060 / 1e6 / 8000)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Everything here runs on one GPU: asked for more, bench.py says so and exits before any GPU work."""
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                         capture_output=True, text=True, timeout=120)
+    assert res.returncode != 0
+    assert "one GPU" in res.stderr and res.stdout.strip() == ""
