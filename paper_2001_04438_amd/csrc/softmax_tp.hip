@@ -66,10 +66,17 @@ static bool valid_unroll(int64_t u, int elem_bytes)
 
 // Rows path: the largest tile (block * unroll vectors per round) that wastes at
 // most 15 % of its last round on the row.
-constexpr int64_t kWaveRowMaxVecs = 256;  // rows up to this many vectors get a wave each ...
-constexpr int64_t kQuadRowMaxVecs = 64;   // ... up to this many a row of 16 lanes (shape.block 16) ...
+// Short rows get a group of lanes each, several rows per workgroup: a wave up to kWaveRowMaxVecs
+// vectors, a row of 16 lanes (shape.block 16) up to kQuadRowMaxVecs, a quad of 4 lanes
+// (shape.block 4) up to kTinyRowMaxVecs [fp32, 16-bit]; the on-chip entry points, which must
+// hold the row in LANES * 4 vectors, switch at their own lengths.  From a sweep of every group
+// size over rows of 1 to 256 vectors.
+constexpr int64_t kWaveRowMaxVecs = 256;
+constexpr int64_t kQuadRowMaxVecs[2] = {64, 128};
+constexpr int64_t kTinyRowMaxVecs[2] = {12, 16};
+constexpr int64_t kOnchipQuadRowMaxVecs = 64;
+constexpr int64_t kOnchipTinyRowMaxVecs = 8;
 constexpr int kQuad = 16;
-constexpr int64_t kTinyRowMaxVecs = 16;   // ... and up to this many a quad of 4 lanes (shape.block 4)
 constexpr int kTiny = 4;
 
 // Workgroup size and loads in flight on the rows path, by row length in 16-byte vectors.  From
@@ -97,24 +104,27 @@ static const RowStep kRowSteps[2][3][5] = {
 };
 
 // algo: 0 Two-Pass, 1 Three-Pass with recomputation, 2 Three-Pass with reloading
-static void rows_shape(const Tuning &g_tune, int64_t nvec, int elem_bytes, int algo,
+static void rows_shape(const Tuning &g_tune, int64_t rows, int64_t nvec, int elem_bytes, int algo,
                        softmax_tp_shape_t *s)
 {
     s->chunk_vecs = 0;
     s->chunks = 1;
-    if (nvec <= kTinyRowMaxVecs && !g_tune.block_rows && !g_tune.unroll_rows) {
-        s->block = kTiny;  // four lanes per row, sixty-four rows per workgroup
-        s->unroll = nvec <= kTiny ? 1 : nvec <= 2 * kTiny ? 2 : 4;
-        return;
-    }
-    if (nvec <= kQuadRowMaxVecs && !g_tune.block_rows && !g_tune.unroll_rows) {
-        s->block = kQuad;  // sixteen lanes per row, sixteen rows per workgroup
-        s->unroll = nvec <= kQuad ? 1 : nvec <= 2 * kQuad ? 2 : 4;
-        return;
-    }
-    if (nvec <= kWaveRowMaxVecs && !g_tune.block_rows && !g_tune.unroll_rows) {
-        s->block = kWave;  // one wave per row, four rows per workgroup
-        s->unroll = nvec <= 2 * kWave ? 2 : 4;
+    const bool group_forced = g_tune.block_rows == kTiny || g_tune.block_rows == kQuad ||
+                              g_tune.block_rows == kWave;
+    if (group_forced || (nvec <= kWaveRowMaxVecs && !g_tune.block_rows)) {
+        // short rows: a group of 4, 16 or 64 lanes per row, several rows per workgroup
+        const int wide = elem_bytes == 4 ? 0 : 1;
+        // (the reloading variant, with a pass that writes y and one that reads it back, does not
+        // gain from rounds of a small group: it moves to the wave at 64 vectors in every format)
+        const int64_t quad_max = algo == 2 ? kQuadRowMaxVecs[0] : kQuadRowMaxVecs[wide];
+        int lanes = nvec <= kTinyRowMaxVecs[wide] ? kTiny : nvec <= quad_max ? kQuad : kWave;
+        if (group_forced) lanes = (int)g_tune.block_rows;
+        // a launch holds fewer than 2^32 threads: very many rows make do with fewer lanes each
+        while (lanes > kTiny && rows > kThreadsMax / lanes)
+            lanes = lanes == kWave ? kQuad : kTiny;
+        int64_t rounds = (nvec + lanes - 1) / lanes;
+        s->block = lanes;
+        s->unroll = g_tune.unroll_rows ? (int32_t)g_tune.unroll_rows : rounds >= 4 ? 4 : (int32_t)rounds;
         return;
     }
     for (const RowStep &step : kRowSteps[elem_bytes == 4 ? 0 : 1][algo]) {
@@ -185,17 +195,17 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
         if (rows > kGridMax || nvec > kChunkVecsMax)
             return TP_ERR_TOO_LARGE;
         p->path = 1;
-        rows_shape(g_tune, nvec, elem_bytes, 0, &p->rows);
-        rows_shape(g_tune, nvec, elem_bytes, 1, &p->rows_recompute);
-        rows_shape(g_tune, nvec, elem_bytes, 2, &p->rows_reload);
+        rows_shape(g_tune, rows, nvec, elem_bytes, 0, &p->rows);
+        rows_shape(g_tune, rows, nvec, elem_bytes, 1, &p->rows_recompute);
+        rows_shape(g_tune, rows, nvec, elem_bytes, 2, &p->rows_reload);
         p->launches = 1;
         for (const softmax_tp_shape_t *sh : {&p->rows, &p->rows_recompute, &p->rows_reload}) {
             // block threads per row, whether that is a workgroup, a wave or a few lanes
             if (rows > kThreadsMax / sh->block)
                 return TP_ERR_TOO_LARGE;
-            if (!((sh->block == kWave || sh->block == kQuad || sh->block == kTiny ||
-                   valid_block(sh->block)) &&
-                  valid_unroll(sh->unroll, elem_bytes)))
+            const bool group = sh->block == kWave || sh->block == kQuad || sh->block == kTiny;
+            if (!(group ? sh->unroll >= 1 && sh->unroll <= 4
+                        : valid_block(sh->block) && valid_unroll(sh->unroll, elem_bytes)))
                 return TP_ERR_TUNING;
         }
         return TP_OK;
@@ -393,15 +403,15 @@ static int run_rows(Algo algo, const softmax_tp_plan_t &plan, const typename IO:
                 return launch(waves_3p_recompute<IO, L, TP_U>, wgrid, wblock, st, x, y, n, rows);
             return launch(waves_3p_reload<IO, L, TP_U>, wgrid, wblock, st, x, y, n, rows);
         };
-        if (shape.block == kWave)
-            return shape.unroll == 2 ? go(ic<kWave>{}, ic<2>{}) : go(ic<kWave>{}, ic<4>{});
-        if (shape.block == kQuad)
-            return shape.unroll == 1   ? go(ic<kQuad>{}, ic<1>{})
-                   : shape.unroll == 2 ? go(ic<kQuad>{}, ic<2>{})
-                                       : go(ic<kQuad>{}, ic<4>{});
-        return shape.unroll == 1   ? go(ic<kTiny>{}, ic<1>{})
-               : shape.unroll == 2 ? go(ic<kTiny>{}, ic<2>{})
-                                   : go(ic<kTiny>{}, ic<4>{});
+        switch (shape.block * 8 + shape.unroll) {
+#define TP_GROUP(L, UU) case L * 8 + UU: return go(ic<L>{}, ic<UU>{});
+            TP_GROUP(kTiny, 1) TP_GROUP(kTiny, 2) TP_GROUP(kTiny, 3) TP_GROUP(kTiny, 4)
+            TP_GROUP(kQuad, 1) TP_GROUP(kQuad, 2) TP_GROUP(kQuad, 3) TP_GROUP(kQuad, 4)
+            TP_GROUP(kWave, 1) TP_GROUP(kWave, 2) TP_GROUP(kWave, 3) TP_GROUP(kWave, 4)
+#undef TP_GROUP
+        default:
+            return TP_ERR_TUNING;
+        }
     }
     const dim3 grid((uint32_t)rows);
     return with_shape<IO>(shape, [&](auto B, auto U) {
@@ -670,7 +680,13 @@ static int run_onchip(int algo, const typename IO::elem *x, typename IO::elem *y
     if (hi <= kWaveRowMaxVecs) {  // short rows: a lane group per row, as on the rows path
         if (rows > kThreadsMax / kWave)
             return TP_ERR_TOO_LARGE;
-        const int lanes = hi <= kQuadRowMaxVecs ? kQuad : kWave;  // a lane holds at most one edge element
+        const Tuning t = tuning();
+        int lanes = hi <= kOnchipTinyRowMaxVecs ? kTiny : hi <= kOnchipQuadRowMaxVecs ? kQuad : kWave;
+        if (t.block_rows == kTiny || t.block_rows == kQuad || t.block_rows == kWave)
+            lanes = (int)t.block_rows;  // for sweeps; the row still has to fit LANES * 4 vectors
+        const int64_t u = (hi + lanes - 1) / lanes;
+        if (u > 4)
+            return TP_ERR_TUNING;
         const int64_t per_group = kShortBlock / lanes;
         const dim3 wgrid((uint32_t)((rows + per_group - 1) / per_group)), wblock(kShortBlock);
         auto go = [&](auto LANES, auto U) {
@@ -679,10 +695,15 @@ static int run_onchip(int algo, const typename IO::elem *x, typename IO::elem *y
                 return launch(waves_onchip<IO, L, TP_U, kOnchipTwoPass>, wgrid, wblock, st, x, y, n, rows);
             return launch(waves_onchip<IO, L, TP_U, kOnchipThreePass>, wgrid, wblock, st, x, y, n, rows);
         };
-        const int64_t u = (hi + lanes - 1) / lanes;
-        if (lanes == kQuad)
-            return u <= 1 ? go(ic<kQuad>{}, ic<1>{}) : u <= 2 ? go(ic<kQuad>{}, ic<2>{}) : go(ic<kQuad>{}, ic<4>{});
-        return u <= 2 ? go(ic<kWave>{}, ic<2>{}) : go(ic<kWave>{}, ic<4>{});
+        switch (lanes * 8 + (int)u) {
+#define TP_GROUP(L, UU) case L * 8 + UU: return go(ic<L>{}, ic<UU>{});
+            TP_GROUP(kTiny, 1) TP_GROUP(kTiny, 2) TP_GROUP(kTiny, 3) TP_GROUP(kTiny, 4)
+            TP_GROUP(kQuad, 1) TP_GROUP(kQuad, 2) TP_GROUP(kQuad, 3) TP_GROUP(kQuad, 4)
+            TP_GROUP(kWave, 1) TP_GROUP(kWave, 2) TP_GROUP(kWave, 3) TP_GROUP(kWave, 4)
+#undef TP_GROUP
+        default:
+            return TP_ERR_TUNING;
+        }
     }
     const int64_t lo = exact ? n / V : (n / V > 0 ? n / V - 1 : 0);
     OnchipShape sh;
@@ -1063,8 +1084,12 @@ int softmax_tp_tune(const char *key, int64_t value)
         if (std::strcmp(key, k.name) != 0)
             continue;
         if (value != 0) {
-            if (k.kind == kBlock && !valid_block(value)) return TP_ERR_TUNING;
-            if (k.kind == kUnroll && !valid_unroll(value, 4)) return TP_ERR_TUNING;
+            const bool rows_key = k.slot == &g_tune_shared.block_rows || k.slot == &g_tune_shared.unroll_rows;
+            if (k.kind == kBlock && !valid_block(value) &&
+                !(rows_key && (value == kTiny || value == kQuad || value == kWave)))
+                return TP_ERR_TUNING;
+            if (k.kind == kUnroll && !valid_unroll(value, 4) && !(rows_key && value == 3))
+                return TP_ERR_TUNING;
             if (k.kind == kThree && value > 2) return TP_ERR_TUNING;
             if (k.slot == &g_tune_shared.fold_max && value > 4096) return TP_ERR_TUNING;
         }

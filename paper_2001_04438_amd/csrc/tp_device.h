@@ -479,6 +479,12 @@ __device__ __forceinline__ Seg<IO> make_seg(const typename IO::elem *x, typename
     return s;
 }
 
+// True if the predicate holds in every active lane of the wave.
+__device__ __forceinline__ bool wave_all(bool p)
+{
+    return __builtin_amdgcn_ballot_w64(p) == __builtin_amdgcn_ballot_w64(true);
+}
+
 template <bool NT, class VEC>
 __device__ __forceinline__ VEC ld(const VEC *p)
 {
@@ -518,7 +524,11 @@ __device__ __forceinline__ void stream(const Seg<IO> &s, P &p, uint32_t tid = th
     const uint32_t cnt = s.cnt;
     uint32_t k = tid;
 
-    for (; k + (uint32_t)((U - 1) * BLOCK) < cnt; k += (uint32_t)(U * BLOCK)) {
+    // Full rounds as long as every lane of the wave has one: a wave whose lanes disagree would run
+    // this loop body for some and the partly filled round below for the others, one after the
+    // other.  When the vote fails a lane has at most U vectors left (the lanes of a wave are in
+    // the same round, and rows that share a wave differ by at most one vector).
+    for (; wave_all(k + (uint32_t)((U - 1) * BLOCK) < cnt); k += (uint32_t)(U * BLOCK)) {
         vec v[U];
 #pragma unroll
         for (int u = 0; u < U; ++u)

@@ -388,8 +388,10 @@ __global__ __launch_bounds__(BLOCK) void rows_onchip(const typename IO::elem *x,
     onchip_row<IO, BLOCK, U, MODE, ALGO>(s, cur, lds);
 }
 
-// The on-chip arrangement for short rows: LANES lanes (a wave, or a row of 16 lanes) hold a
-// softmax row of at most LANES * U vectors in their registers; reductions as in waves_*.
+// The on-chip arrangement for short rows: LANES lanes (a wave, a row of 16 lanes or a quad)
+// hold a softmax row of at most LANES * U vectors in their registers; reductions as in
+// waves_*.  The elements before the first and after the last whole vector of a row (at most
+// 2 (V - 1)) are spread over the lanes, E of them per lane.
 template <class IO, int LANES, int U, int ALGO>
 __global__ __launch_bounds__(kShortBlock) void waves_onchip(const typename IO::elem *x,
                                                             typename IO::elem *y, int64_t n,
@@ -397,6 +399,7 @@ __global__ __launch_bounds__(kShortBlock) void waves_onchip(const typename IO::e
 {
     TP_SHORT_ROW_PROLOGUE
     constexpr int V = IO::V;
+    constexpr int E = V == 1 ? 1 : (2 * (V - 1) + LANES - 1) / LANES;
     const typename IO::vec *xb = s.xv + s.vb;
     typename IO::vec *yb = s.yv + s.vb;
     typename IO::vec v[U];
@@ -406,15 +409,23 @@ __global__ __launch_bounds__(kShortBlock) void waves_onchip(const typename IO::e
         own[u] = lane + (uint32_t)(u * LANES) < s.cnt;
         v[u] = own[u] ? ld<kLoadStream>(xb + lane + u * LANES) : IO::zero();
     }
-    const int64_t nedge = s.head + (s.n - s.tail0);
-    const bool edge = (int64_t)lane < nedge;
-    const int64_t iedge = (int)lane < s.head ? (int64_t)lane : s.tail0 + ((int64_t)lane - s.head);
-    const float x_edge = edge ? IO::load1(s.xrow + iedge) : 0.f;
-    float e[U * V], e_edge = 0.f;
+    const int nedge = s.edges ? s.head + (int)(s.n - s.tail0) : 0;
+    bool edge[E];
+    int64_t iedge[E];
+    float x_edge[E], e_edge[E];
+#pragma unroll
+    for (int k = 0; k < E; ++k) {
+        const int j = (int)lane + k * LANES;
+        edge[k] = j < nedge;
+        iedge[k] = j < s.head ? (int64_t)j : s.tail0 + (j - s.head);
+        x_edge[k] = edge[k] ? IO::load1(s.xrow + iedge[k]) : 0.f;
+        e_edge[k] = 0.f;
+    }
+    float e[U * V];
     if constexpr (ALGO == kOnchipTwoPass) {
         using Acc = PairSumOf<IO>;
         Acc acc;
-        typename Acc::token g[U];
+        typename Acc::token g[U], g_edge[E];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (own[u]) {
@@ -424,9 +435,12 @@ __global__ __launch_bounds__(kShortBlock) void waves_onchip(const typename IO::e
             }
             g[u] = acc.exponent();
         }
-        if (edge)
-            acc.template group<1>(&x_edge, &e_edge);
-        const typename Acc::token g_edge = acc.exponent();
+#pragma unroll
+        for (int k = 0; k < E; ++k) {
+            if (edge[k])
+                acc.template group<1>(&x_edge[k], &e_edge[k]);
+            g_edge[k] = acc.exponent();
+        }
         float m_sum, n_sum;
         acc.finish(m_sum, n_sum);
         lanes_pair<LANES>(m_sum, n_sum);
@@ -442,8 +456,10 @@ __global__ __launch_bounds__(kShortBlock) void waves_onchip(const typename IO::e
                 st<kStoreStream>(yb + lane + u * LANES, IO::pack(o));
             }
         }
-        if (edge)
-            IO::store1(s.yrow + iedge, e_edge * Acc::factor(lambda, g_edge, n_sum));
+#pragma unroll
+        for (int k = 0; k < E; ++k)
+            if (edge[k])
+                IO::store1(s.yrow + iedge[k], e_edge[k] * Acc::factor(lambda, g_edge[k], n_sum));
     } else {
         float mx = -__builtin_inff();
 #pragma unroll
@@ -456,8 +472,10 @@ __global__ __launch_bounds__(kShortBlock) void waves_onchip(const typename IO::e
                     mx = fmaxf(mx, f[i]);
             }
         }
-        if (edge)
-            mx = fmaxf(mx, x_edge);
+#pragma unroll
+        for (int k = 0; k < E; ++k)
+            if (edge[k])
+                mx = fmaxf(mx, x_edge[k]);
         const float mu = lanes_max<LANES>(mx);
         float part = 0.f;
 #pragma unroll
@@ -471,9 +489,12 @@ __global__ __launch_bounds__(kShortBlock) void waves_onchip(const typename IO::e
                 part += tree_sum<V>(t);
             }
         }
-        if (edge) {
-            e_edge = exp_nonpos_as<IO::kIntExp>(x_edge - mu);
-            part += e_edge;
+#pragma unroll
+        for (int k = 0; k < E; ++k) {
+            if (edge[k]) {
+                e_edge[k] = exp_nonpos_as<IO::kIntExp>(x_edge[k] - mu);
+                part += e_edge[k];
+            }
         }
         const float lambda = 1.0f / lanes_sum<LANES>(part);
 #pragma unroll
@@ -486,8 +507,10 @@ __global__ __launch_bounds__(kShortBlock) void waves_onchip(const typename IO::e
                 st<kStoreStream>(yb + lane + u * LANES, IO::pack(o));
             }
         }
-        if (edge)
-            IO::store1(s.yrow + iedge, lambda * e_edge);
+#pragma unroll
+        for (int k = 0; k < E; ++k)
+            if (edge[k])
+                IO::store1(s.yrow + iedge[k], lambda * e_edge[k]);
     }
 }
 

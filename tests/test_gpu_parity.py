@@ -212,13 +212,14 @@ def test_edge_lengths_bf16(gpu, oracle_mod):
 
 @pytest.mark.parametrize("name,tol", ALGOS_F32)
 def test_short_rows_one_lane_group_each(gpu, oracle_mod, name, tol):
-    """Rows of at most 16 vectors get a quad of lanes each (64 rows per workgroup), up to 64 vectors
-    16 lanes each (16 rows per workgroup), up to 256 vectors a wave each (4 rows per workgroup): every
-    unroll of each, row counts that leave groups idle."""
+    """Rows of at most 12 vectors (16-bit: 16) get a quad of lanes each (64 rows per workgroup), up to
+    64 vectors (16-bit: 128) 16 lanes each (16 rows per workgroup), up to 256 vectors a wave each (4 rows
+    per workgroup): every unroll of each, row counts that leave groups idle."""
     rng = np.random.default_rng(83)
-    for rows, n, lanes in ((1001, 100, 16), (4097, 256, 16), (3000, 33, 4), (50, 1, 4), (17, 64, 4),
-                           (1, 129, 16), (33, 7, 4), (260, 255, 16), (5000, 16, 4), (777, 61, 4), (65, 65, 16),
-                           (6, 1024, 64), (513, 1021, 64), (1003, 257, 64), (5, 600, 64)):
+    for rows, n, lanes in ((1001, 100, 16), (4097, 256, 16), (3000, 33, 4), (50, 1, 4), (17, 64, 16),
+                           (1, 129, 16), (33, 7, 4), (260, 255, 16), (5000, 16, 4), (777, 61, 16), (65, 65, 16),
+                           (901, 48, 4), (333, 45, 4), (444, 92, 16), (555, 380, 64), (99, 190, 16),
+                           (6, 1024, 64), (513, 1021, 64), (1003, 257, 64), (5, 600, 64), (1234, 768, 64)):
         assert gpu.softmax_tp_plan(rows, n).rows.block == lanes
         x = rng.normal(0, 5, size=(rows, n)).astype(np.float32)
         _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
@@ -249,8 +250,9 @@ def test_very_many_rows(gpu, oracle_mod, name, tol):
 def test_short_rows_one_wave_each_bf16(gpu, oracle_mod):
     rng = np.random.default_rng(84)
     for name in ("softmax2p_bf16io", "softmax3p_recompute_bf16io", "softmax3p_reload_bf16io"):
-        for rows, n in ((1001, 100), (4097, 512), (7, 2048), (513, 2041), (300, 513), (9, 8), (2000, 37)):
-            assert gpu.softmax_tp_plan(rows, n, 2).rows.block == (4 if n <= 128 else 16 if n <= 512 else 64)
+        for rows, n in ((1001, 100), (4097, 512), (7, 2048), (513, 2041), (300, 513), (9, 8), (2000, 37),
+                        (1500, 96), (700, 192), (600, 768), (450, 1000), (350, 1536), (3333, 48)):
+            assert gpu.softmax_tp_plan(rows, n, 2).rows.block == (4 if n <= 128 else 16 if n <= 1024 else 64)
             x = workloads.f32_to_bf16_bits(rng.normal(0, 5, size=(rows, n)).astype(np.float32)).reshape(rows, n)
             _check(oracle_mod, x, _run(getattr(gpu, name), x), TOL_BF16, bf16=True)
         x = workloads.cfg5(rows=77, n=1003)
@@ -455,6 +457,28 @@ def test_onchip_bf16(gpu, oracle_mod, name):
     for off in (1, 5, 7):
         _check(oracle_mod, x, _run(fn, x, x_off=off, y_off=off), TOL_BF16, bf16=True)
     _check(oracle_mod, x, _run(fn, x, inplace=True), TOL_BF16, bf16=True)
+
+
+@pytest.mark.parametrize("fmt", ["f32", "bf16", "f16"])
+def test_onchip_short_rows_every_lane_group(gpu, oracle_mod, fmt):
+    """Rows of at most 256 vectors are held by a quad, a row of 16 lanes or a wave: every group with
+    one to four vectors per lane, many rows per wave, bases that leave up to 2 (V - 1) edge elements
+    (more than a quad has lanes) and row counts that leave groups idle."""
+    rng = np.random.default_rng(92)
+    V = 4 if fmt == "f32" else 8
+    names = {"f32": ONCHIP_F32, "bf16": [(n, TOL_BF16) for n in ONCHIP_BF16], "f16": ONCHIP_F16}[fmt]
+    for nvec in (1, 2, 3, 4, 5, 7, 8, 9, 12, 16, 17, 31, 33, 48, 64, 65, 100, 129, 190, 255, 256):
+        for n in {nvec * V, max(1, nvec * V - V // 2 - 1)}:
+            rows = 1000 // nvec + 7
+            x = (rng.normal(0, 5, size=(rows, n)) + rng.uniform(-40, 40, size=(rows, 1))).astype(np.float32)
+            if fmt == "bf16":
+                x = workloads.f32_to_bf16_bits(x).reshape(rows, n)
+            elif fmt == "f16":
+                x = workloads.f32_to_f16_bits(x).reshape(rows, n)
+            for name, tol in names:
+                for off in (0, 1, V - 1):
+                    y = _run(getattr(gpu, name), x, x_off=off, y_off=off)
+                    _check(oracle_mod, x, y, tol, bf16=fmt == "bf16", f16=fmt == "f16")
 
 
 def test_onchip_limits(gpu):

@@ -145,16 +145,21 @@ def test_planner_covers_odd_shapes(B):
             if p.path == 1:
                 assert n * s <= 256 * 1024 and p.rows.block in (4, 16, 64, 256, 512, 1024)
                 nvec = -(-n // V)
-                assert (p.rows.block == 4) == (nvec <= 16)           # tiny rows: a quad of lanes each
-                assert (p.rows.block == 16) == (16 < nvec <= 64)     # very short rows: 16 lanes each
-                assert (p.rows.block == 64) == (64 < nvec <= 256)    # short rows: a wave each
-                if p.rows.block in (4, 16):
-                    assert p.rows.unroll * p.rows.block >= nvec and p.rows.unroll in (1, 2, 4)
+                tiny, quad = (12, 64) if s == 4 else (16, 128)
+                assert (p.rows.block == 4) == (nvec <= tiny)            # tiny rows: a quad of lanes each
+                assert (p.rows.block == 16) == (tiny < nvec <= quad)    # very short rows: 16 lanes each
+                assert (p.rows.block == 64) == (quad < nvec <= 256)     # short rows: a wave each
+                if p.rows.block < 256:     # as many loads in flight as the row has rounds, four at most
+                    assert p.rows.unroll == min(4, -(-nvec // p.rows.block))
                 for other in (p.rows_recompute, p.rows_reload):
                     # the lane-group shapes are shared; workgroup shapes may differ per algorithm
                     assert (other.block < 256) == (p.rows.block < 256)
                     if p.rows.block < 256:
-                        assert (other.block, other.unroll) == (p.rows.block, p.rows.unroll)
+                        # the lane groups are shared, but for 16-bit rows of 65 to 128 vectors, which
+                        # the reloading variant gives a wave each
+                        wave_early = other is p.rows_reload and s == 2 and 64 < nvec <= 128
+                        assert other.block == (64 if wave_early else p.rows.block)
+                        assert other.unroll == min(4, -(-nvec // other.block))
                     else:
                         assert other.block in (256, 512, 1024) and other.unroll in ((2, 4, 8) if s == 4 else (2, 4))
                     assert other.chunks == 1 and other.chunk_vecs == 0
@@ -171,7 +176,8 @@ def test_planner_covers_odd_shapes(B):
     # a launch holds fewer than 2^32 threads: shapes beyond that are refused, not truncated
     assert big.map.chunks * big.map.block < 2 ** 32 and big.map.chunk_vecs > 2048
     assert B.softmax_tp_plan(1 << 29, 64).rows.block == 4       # 2^31 threads: still one launch
-    for rows, n in ((1 << 23, 8192), (1, 1 << 60), (1 << 31, 64), (1 << 27, 300)):
+    assert B.softmax_tp_plan(1 << 27, 300).rows.block == 16     # a wave each would be 2^33 threads
+    for rows, n in ((1 << 23, 8192), (1, 1 << 60), (1 << 31, 64), (1 << 30, 300)):
         with pytest.raises(B.SoftmaxTpError) as e:
             B.softmax_tp_plan(rows, n)
         assert e.value.code == B.TP_ERR_TOO_LARGE
@@ -193,7 +199,7 @@ def test_tuning_keys(B):
     assert (p.map.block, p.map.unroll, p.map.chunk_vecs) == (256, 8, 3 * 256 * 8)
     with pytest.raises(B.SoftmaxTpError):          # bf16 keeps at most 4 loads in flight
         B.softmax_tp_plan(2, 10_000_000, 2)
-    for key, bad in (("block_map", 300), ("unroll_rows", 3), ("path", 7), ("no_such_key", 1),
+    for key, bad in (("block_map", 300), ("unroll_map", 3), ("unroll_rows", 5), ("block_rows", 32), ("path", 7), ("no_such_key", 1),
                      ("direction", 3)):
         with pytest.raises(B.SoftmaxTpError):
             B.softmax_tp_tune(key, bad)
