@@ -215,7 +215,8 @@ TP_API int softmax_tp_stream_scale_f32(const float *x, float *y, float a, int64_
 /* ----- planning, workspace, tuning (host side) ----- */
 
 typedef struct {
-    int32_t block;      /* threads per workgroup */
+    int32_t block;      /* threads per workgroup; on the rows path 4, 16 or 64 stand for that many
+                           lanes per row, several rows sharing a workgroup of 256 threads */
     int32_t unroll;     /* 16-byte loads in flight per thread */
     int64_t chunk_vecs; /* 16-byte vectors per workgroup (0 on the rows path: the whole row) */
     int64_t chunks;     /* workgroups per row */
@@ -261,8 +262,10 @@ TP_API int softmax_tp_plan(int64_t rows, int64_t n, int32_t elem_bytes, int32_t 
  *   "fold_max"        most partial results per row that a consuming pass folds by itself;
  *                     more than that go through a merge kernel first (at most 4096)
  * block is 256, 512 or 1024; unroll 2, 4 or 8 (16-bit formats: 2 or 4); in addition the
- * pair block 128, unroll 1.  value 0 restores the
- * default.  May be called while other threads plan or launch (each call reads the settings
+ * pair block 128, unroll 1.  "block_rows" also takes 4, 16 or 64: a group of that many lanes
+ * per row, several rows per workgroup (what rows of at most 256 vectors get by default), with
+ * "unroll_rows" 1 to 4; the on-chip entry points follow such a "block_rows" for rows that fit
+ * four vectors per lane.  value 0 restores the default.  May be called while other threads plan or launch (each call reads the settings
  * under a lock and sees every key either before or after the change), but a call that
  * overlaps a retune may mix old and new keys: retune between calls when that matters.
  */
