@@ -64,14 +64,14 @@ static bool valid_unroll(int64_t u, int elem_bytes)
     return u == 1 || u == 2 || u == 4 || (u == 8 && elem_bytes == 4);
 }
 
-// Rows path: the largest tile (block * unroll vectors per round) that wastes at
-// most 15 % of its last round on the row.
-// Short rows get a group of lanes each, several rows per workgroup: a wave up to kWaveRowMaxVecs
-// vectors, a row of 16 lanes (shape.block 16) up to kQuadRowMaxVecs, a quad of 4 lanes
-// (shape.block 4) up to kTinyRowMaxVecs [fp32, 16-bit]; the on-chip entry points, which must
-// hold the row in LANES * 4 vectors, switch at their own lengths.  From a sweep of every group
-// size over rows of 1 to 256 vectors.
-constexpr int64_t kWaveRowMaxVecs = 256;
+// Rows path.  Short rows get a group of lanes each, several rows per workgroup: a wave up to
+// kWaveRowMaxVecs vectors (beyond 256 in a second round: up to these lengths that still beats
+// a workgroup of 256 threads with its barriers), a row of 16 lanes (shape.block 16) up to
+// kQuadRowMaxVecs, a quad of 4 lanes (shape.block 4) up to kTinyRowMaxVecs [fp32, 16-bit]; the
+// on-chip entry points, which must hold the row in LANES * 4 vectors, switch at their own
+// lengths.  From sweeps of every group size over rows of 1 to 1536 vectors.
+constexpr int64_t kWaveRowMaxVecs[2][3] = {{352, 352, 272}, {512, 512, 304}};  // [format][algorithm]
+constexpr int64_t kOnchipWaveRowMaxVecs = 256;  // a wave holds four vectors per lane
 constexpr int64_t kQuadRowMaxVecs[2] = {64, 128};
 constexpr int64_t kTinyRowMaxVecs[2] = {12, 16};
 constexpr int64_t kOnchipQuadRowMaxVecs = 64;
@@ -111,7 +111,7 @@ static void rows_shape(const Tuning &g_tune, int64_t rows, int64_t nvec, int ele
     s->chunks = 1;
     const bool group_forced = g_tune.block_rows == kTiny || g_tune.block_rows == kQuad ||
                               g_tune.block_rows == kWave;
-    if (group_forced || (nvec <= kWaveRowMaxVecs && !g_tune.block_rows)) {
+    if (group_forced || (nvec <= kWaveRowMaxVecs[elem_bytes == 4 ? 0 : 1][algo] && !g_tune.block_rows)) {
         // short rows: a group of 4, 16 or 64 lanes per row, several rows per workgroup
         const int wide = elem_bytes == 4 ? 0 : 1;
         // (the reloading variant, with a pass that writes y and one that reads it back, does not
@@ -677,7 +677,7 @@ static int run_onchip(int algo, const typename IO::elem *x, typename IO::elem *y
     const bool exact = ((uintptr_t)x % 16) == 0 && n % V == 0;
     const int64_t hi = (n + V - 1) / V;
     hipStream_t st = (hipStream_t)stream;
-    if (hi <= kWaveRowMaxVecs) {  // short rows: a lane group per row, as on the rows path
+    if (hi <= kOnchipWaveRowMaxVecs) {  // short rows: a lane group per row, as on the rows path
         if (rows > kThreadsMax / kWave)
             return TP_ERR_TOO_LARGE;
         const Tuning t = tuning();

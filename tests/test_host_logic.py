@@ -145,24 +145,24 @@ def test_planner_covers_odd_shapes(B):
             if p.path == 1:
                 assert n * s <= 256 * 1024 and p.rows.block in (4, 16, 64, 256, 512, 1024)
                 nvec = -(-n // V)
-                tiny, quad = (12, 64) if s == 4 else (16, 128)
+                tiny, quad, wave, wave_reload = (12, 64, 352, 272) if s == 4 else (16, 128, 512, 304)
                 assert (p.rows.block == 4) == (nvec <= tiny)            # tiny rows: a quad of lanes each
                 assert (p.rows.block == 16) == (tiny < nvec <= quad)    # very short rows: 16 lanes each
-                assert (p.rows.block == 64) == (quad < nvec <= 256)     # short rows: a wave each
-                if p.rows.block < 256:     # as many loads in flight as the row has rounds, four at most
-                    assert p.rows.unroll == min(4, -(-nvec // p.rows.block))
-                for other in (p.rows_recompute, p.rows_reload):
-                    # the lane-group shapes are shared; workgroup shapes may differ per algorithm
-                    assert (other.block < 256) == (p.rows.block < 256)
-                    if p.rows.block < 256:
-                        # the lane groups are shared, but for 16-bit rows of 65 to 128 vectors, which
-                        # the reloading variant gives a wave each
-                        wave_early = other is p.rows_reload and s == 2 and 64 < nvec <= 128
-                        assert other.block == (64 if wave_early else p.rows.block)
-                        assert other.unroll == min(4, -(-nvec // other.block))
+                assert (p.rows.block == 64) == (quad < nvec <= wave)    # short rows: a wave each
+                assert (p.rows_recompute.block < 256) == (nvec <= wave)
+                assert (p.rows_reload.block < 256) == (nvec <= wave_reload)
+                for shape in (p.rows, p.rows_recompute, p.rows_reload):
+                    if shape.block < 256:   # as many loads in flight as the row has rounds, four at most
+                        assert shape.unroll == min(4, -(-nvec // shape.block))
                     else:
-                        assert other.block in (256, 512, 1024) and other.unroll in ((2, 4, 8) if s == 4 else (2, 4))
-                    assert other.chunks == 1 and other.chunk_vecs == 0
+                        assert shape.block in (256, 512, 1024) and shape.unroll in ((2, 4, 8) if s == 4 else (2, 4))
+                    assert shape.chunks == 1 and shape.chunk_vecs == 0
+                # the lane groups are the same for every algorithm, but the reloading variant moves to
+                # the wave at 64 vectors in every format
+                assert p.rows_recompute.block == p.rows.block or p.rows.block >= 256
+                if p.rows_reload.block < 256:
+                    wave_early = s == 2 and 64 < nvec <= 128
+                    assert p.rows_reload.block == (64 if wave_early else p.rows.block)
                 if p.rows.block >= 256:
                     # a lane sees at least one and at most 32 rounds of loads (element-wise 16-bit rows)
                     assert 1 <= -(-nvec // (p.rows.block * p.rows.unroll)) <= 32
