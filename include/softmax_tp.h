@@ -261,6 +261,10 @@ TP_API int softmax_tp_plan(int64_t rows, int64_t n, int32_t elem_bytes, int32_t 
  *   "nt_first"        1: first read of x cacheable; 2: non-temporal; default: by size
  *   "fold_max"        most partial results per row that a consuming pass folds by itself;
  *                     more than that go through a merge kernel first (at most 4096)
+ *   "nt_store"        rows on groups of 4 or 16 lanes: 1 stores y without the non-temporal
+ *                     hint, 2 with it; default: without it for rows under 1 KiB (on-chip entry
+ *                     points: under 128 bytes) whose length neither divides nor is a multiple
+ *                     of 128 bytes, so that neighbouring rows share cache lines unevenly
  * block is 256, 512 or 1024; unroll 2, 4 or 8 (16-bit formats: 2 or 4); in addition the
  * pair block 128, unroll 1.  "block_rows" also takes 4, 16 or 64: a group of that many lanes
  * per row, several rows per workgroup (what rows of at most 256 vectors get by default), with

@@ -523,7 +523,6 @@ __device__ __forceinline__ void stream(const Seg<IO> &s, P &p, uint32_t tid = th
     vec *yb = s.yv + s.vb;
     const uint32_t cnt = s.cnt;
     uint32_t k = tid;
-
     // Full rounds as long as every lane of the wave has one: a wave whose lanes disagree would run
     // this loop body for some and the partly filled round below for the others, one after the
     // other.  When the vote fails a lane has at most U vectors left (the lanes of a wave are in

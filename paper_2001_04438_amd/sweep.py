@@ -8,12 +8,15 @@ storage (the one regime where the outcome differs: bf16 rows are bound by vector
           where the one-workgroup-per-row path (second read served by L2) hands over to the
           chunked path (every read from memory)
   single  one vector of N = 2^10 ... 2^28 elements
+  ragged  the same 2^26 elements as rows of lengths that are not powers of two (24 ... 57000
+          elements, among them 1.5 x 2^k and class counts like 1000 and 21846), which leave
+          the last round of a lane group or a workgroup partly filled
 
 Each point is the median of `--iters` calls, every call bracketed by events on the launch
 stream, rotating over enough buffer sets to exceed 1 GiB so that no call finds its input in
 a cache.  Output: markdown tables on stdout.
 
-    python -m paper_2001_04438_amd.sweep [--iters 20] [--which batch|single|both] [--dtype f32|bf16|both]
+    python -m paper_2001_04438_amd.sweep [--iters 20] [--which batch|single|ragged|all] [--dtype f32|bf16|both]
 """
 from __future__ import annotations
 
@@ -24,6 +27,7 @@ VARIANTS = (("2p", "softmax2p", 3), ("3p_recompute", "softmax3p_recompute", 4),
             ("3p_reload", "softmax3p_reload", 5), ("2p_onchip", "softmax2p_onchip", 2))
 SUFFIX = {"f32": "_f32", "bf16": "_bf16io"}
 ONCHIP_MAX_N = 32768
+RAGGED_N = (24, 96, 100, 192, 384, 768, 1000, 1100, 1300, 3000, 5000, 10000, 21846, 28000, 40000, 57000)
 
 
 def median_ms(torch, fn, iters, sets):
@@ -89,7 +93,7 @@ def table(torch, B, shapes, iters, dtype):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--iters", type=int, default=20)
-    ap.add_argument("--which", default="both", choices=["batch", "single", "both"])
+    ap.add_argument("--which", default="all", choices=["batch", "single", "ragged", "both", "all"])
     ap.add_argument("--dtype", default="both", choices=["f32", "bf16", "both"])
     args = ap.parse_args()
     import torch
@@ -98,14 +102,18 @@ def main():
         sys.exit("the sweep needs a GPU")
     B.lib()
     for dtype in (("f32", "bf16") if args.dtype == "both" else (args.dtype,)):
-        if args.which in ("batch", "both"):
+        if args.which in ("batch", "both", "all"):
             print(f"## batch, {dtype}: 2^26 elements as rows x N\n")
             table(torch, B, [((1 << 26) >> e, 1 << e) for e in range(8, 27, 2)] +
                   [((1 << 26) >> 15, 1 << 15), ((1 << 26) >> 17, 1 << 17)], args.iters, dtype)
             print()
-        if args.which in ("single", "both"):
+        if args.which in ("single", "both", "all"):
             print(f"## single vector of N elements, {dtype}\n")
             table(torch, B, [(1, 1 << e) for e in range(10, 29, 2)], args.iters, dtype)
+            print()
+        if args.which in ("ragged", "all"):
+            print(f"## ragged rows, {dtype}: about 2^26 elements as rows x N\n")
+            table(torch, B, [((1 << 26) // n, n) for n in RAGGED_N], args.iters, dtype)
             print()
     B.softmax_tp_release()
 

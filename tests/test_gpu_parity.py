@@ -238,6 +238,25 @@ def test_short_rows_one_lane_group_each(gpu, oracle_mod, name, tol):
     assert np.isnan(y[5]).all() and np.isfinite(np.delete(y, 5, axis=0)).all()
 
 
+def test_short_rows_with_and_without_the_store_hint(gpu, oracle_mod):
+    """Rows on 4 or 16 lanes store y with or without the non-temporal hint depending on how they
+    share cache lines; both variants of every kernel, forced through the tuning key, and the default."""
+    rng = np.random.default_rng(98)
+    try:
+        for setting in (1, 2, 0):
+            gpu.softmax_tp_tune("nt_store", setting)
+            for rows, n in ((3001, 25), (2000, 100), (999, 64), (700, 250), (300, 1000)):
+                x = rng.normal(0, 5, size=(rows, n)).astype(np.float32)
+                for name, tol in ALGOS_F32 + ONCHIP_F32:
+                    _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
+                    _check(oracle_mod, x, _run(getattr(gpu, name), x, inplace=True), tol)
+                xb = workloads.f32_to_bf16_bits(x).reshape(x.shape)
+                for name in ("softmax2p_bf16io", "softmax3p_recompute_bf16io", "softmax3p_reload_bf16io") + tuple(ONCHIP_BF16):
+                    _check(oracle_mod, xb, _run(getattr(gpu, name), xb, x_off=3, y_off=3), TOL_BF16, bf16=True)
+    finally:
+        gpu.softmax_tp_tune_reset()
+
+
 @pytest.mark.parametrize("name,tol", ALGOS_F32)
 def test_very_many_rows(gpu, oracle_mod, name, tol):
     """Grids of hundreds of thousands of workgroups: one wave per row and one workgroup per row."""
