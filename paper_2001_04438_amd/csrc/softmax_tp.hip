@@ -628,9 +628,10 @@ struct OnchipShape {
 
 // A row must fit block * unroll vectors.  lo / hi bound the number of whole vectors a row
 // can have (it depends on where the row starts relative to a 16-byte boundary).  Candidates
-// are tiles the rows fill exactly (kTileFull) and tiles whose first unroll - 1 slots every
-// row fills (kTileMostly); the one with the least padding wins, then the unroll closest to
-// 4, then the smaller block.  If neither kind exists: the catch-all with 1024 threads.
+// are tiles the rows fill exactly (kTileFull), tiles whose first unroll - 1 slots every row
+// fills (kTileMostly) and tiles that check every slot (kTileAny); the one with the least
+// padding wins (a row of 513 vectors takes 256 x 3, not 1024 x 1 with half the threads idle),
+// then the unroll closest to 4, then the cheaper kind, then the smaller block.
 static bool onchip_shape(int64_t lo, int64_t hi, bool exact, int unroll_max, OnchipShape *out)
 {
     static const int blocks[] = {256, 512, 1024};
@@ -646,22 +647,17 @@ static bool onchip_shape(int64_t lo, int64_t hi, bool exact, int unroll_max, Onc
         else if ((u - 1) * b <= lo)
             mode = kTileMostly;
         else
-            continue;
+            mode = kTileAny;
         const int64_t pad = b * u - hi;
-        const int64_t key = (pad << 8) + ((u > 4 ? u - 4 : 4 - u) << 2) + (mode == kTileFull ? 0 : 1);
+        const int64_t key = (pad << 8) + ((u > 4 ? u - 4 : 4 - u) << 2) +
+                            (mode == kTileFull ? 0 : mode == kTileMostly ? 1 : 2);
         if (!found || key < best_key) {
             found = true;
             best_key = key;
             *out = OnchipShape{b, (int)u, mode};
         }
     }
-    if (found)
-        return true;
-    const int64_t u = (hi + 1023) / 1024;
-    if (u > unroll_max)
-        return false;
-    *out = OnchipShape{1024, (int)(u < 1 ? 1 : u), kTileAny};
-    return true;
+    return found;
 }
 
 template <class IO, int B, int U, int MODE>
@@ -685,10 +681,7 @@ static int launch_onchip_mode(int mode, int algo, const typename IO::elem *x,
     }
     if (mode == kTileMostly)
         return launch_onchip<IO, B, U, kTileMostly>(algo, x, y, rows, n, st);
-    if constexpr (B == 1024)
-        return launch_onchip<IO, B, U, kTileAny>(algo, x, y, rows, n, st);
-    else
-        return TP_ERR_TUNING;
+    return launch_onchip<IO, B, U, kTileAny>(algo, x, y, rows, n, st);
 }
 
 template <class IO>

@@ -449,7 +449,8 @@ def test_onchip_f32(gpu, oracle_mod, name, tol):
     cases = [workloads.cfg1(), workloads.cfg1(probes=True), workloads.cfg2(rows=37, n=32768),
              workloads.cfg2(rows=700, n=8192),          # more rows than resident workgroups
              workloads.cfg2(rows=2100, n=1000)]
-    for n in EDGE_N + [8191, 8193, 20000, 28001, 32767]:
+    # (1026, 2050, 4100, 8197: a vector or two more than a power of two, which no tile fills slot by slot)
+    for n in EDGE_N + [1026, 2050, 4100, 8191, 8193, 8197, 20000, 28001, 32767]:
         cases.append(rng.normal(0, 6, size=(3, n)).astype(np.float32))
     for x in cases:
         _check(oracle_mod, x, _run(fn, x), tol)
@@ -471,7 +472,7 @@ def test_onchip_bf16(gpu, oracle_mod, name):
     rng = np.random.default_rng(91)
     cases = [workloads.cfg5(rows=61, n=21846), workloads.cfg5(rows=1500, n=3000),
              workloads.cfg5(rows=5, n=32768)]
-    for n in EDGE_N + [16383, 21841, 32767]:
+    for n in EDGE_N + [2052, 4100, 8200, 16383, 16390, 21841, 32767]:
         cases.append(workloads.f32_to_bf16_bits(rng.normal(0, 6, size=(3, n)).astype(np.float32)).reshape(3, n))
     for x in cases:
         _check(oracle_mod, x, _run(fn, x), TOL_BF16, bf16=True)
