@@ -128,7 +128,10 @@ TP_API int softmax3p_reload_f16io(const uint16_t *x, uint16_t *y, int64_t rows, 
  * (Sections 6.4 and 7), the Two-Pass algorithm has no bandwidth advantage left to offer.
  * Kept as an entry point of its own so that its throughput is never mistaken for the
  * three-traversal algorithm's.  x and y must be congruent modulo 16 bytes
- * (TP_ERR_ALIGN otherwise); longer rows give TP_ERR_TOO_LARGE.
+ * (TP_ERR_ALIGN otherwise); longer rows give TP_ERR_TOO_LARGE.  Rows of at most 9 fp32 or 16
+ * 16-bit elements are handled by one lane each with the kernels of softmax2p_* (of
+ * softmax3p_recompute_* for the softmax3p_onchip_* entry points): the lane re-reads, and
+ * re-evaluates, the one or two cache lines it has just read, so memory traffic is the same.
  */
 #define TP_ONCHIP_MAX_N 32768
 TP_API int softmax2p_onchip_f32(const float *x, float *y, int64_t rows, int64_t n, void *stream);
@@ -215,7 +218,7 @@ TP_API int softmax_tp_stream_scale_f32(const float *x, float *y, float a, int64_
 /* ----- planning, workspace, tuning (host side) ----- */
 
 typedef struct {
-    int32_t block;      /* threads per workgroup; on the rows path 4, 16 or 64 stand for that many
+    int32_t block;      /* threads per workgroup; on the rows path 1, 4, 16 or 64 stand for that many
                            lanes per row, several rows sharing a workgroup of 256 threads */
     int32_t unroll;     /* 16-byte loads in flight per thread */
     int64_t chunk_vecs; /* 16-byte vectors per workgroup (0 on the rows path: the whole row) */
@@ -225,7 +228,10 @@ typedef struct {
 typedef struct {
     int32_t path;          /* 1: one workgroup per row, every pass in a single launch;
                               2: rows cut into chunks, one launch per pass + small merge launches */
-    int32_t vector_elems;  /* elements per access: 4 (fp32) / 8 (bf16), or 1 when unaligned */
+    int32_t vector_elems;  /* elements per access: 4 (fp32) / 8 (16-bit), or 1 when x and y are not
+                              congruent modulo 16 bytes, and for rows of at most 9 fp32 / 16 16-bit
+                              elements (one lane per row) whose length is not a multiple of 16 bytes;
+                              a call also uses 1 for such rows if x itself is not 16-byte aligned */
     int32_t launches;      /* kernel launches of the Two-Pass call */
     int32_t merge_kernel;  /* path 2: 1 if a row has more than 128 chunk partials, which a small
                               kernel of its own then merges; 0 if the next pass folds them itself */
@@ -266,7 +272,7 @@ TP_API int softmax_tp_plan(int64_t rows, int64_t n, int32_t elem_bytes, int32_t 
  *                     points: under 128 bytes) whose length neither divides nor is a multiple
  *                     of 128 bytes, so that neighbouring rows share cache lines unevenly
  * block is 256, 512 or 1024; unroll 2, 4 or 8 (16-bit formats: 2 or 4); in addition the
- * pair block 128, unroll 1.  "block_rows" also takes 4, 16 or 64: a group of that many lanes
+ * pair block 128, unroll 1.  "block_rows" also takes 1, 4, 16 or 64: a group of that many lanes
  * per row, several rows per workgroup (what rows of at most 256 vectors get by default), with
  * "unroll_rows" 1 to 4; the on-chip entry points follow such a "block_rows" for rows that fit
  * four vectors per lane.  value 0 restores the default.  May be called while other threads plan or launch (each call reads the settings

@@ -99,7 +99,7 @@ class Plan(ctypes.Structure):
 
 TUNE_KEYS = ("path", "block_rows", "unroll_rows", "block_reduce", "unroll_reduce", "target_reduce",
              "block_map", "unroll_map", "tiles_map", "block_mapsum", "unroll_mapsum", "tiles_mapsum",
-             "direction", "nt_first", "fold_max", "nt_store")
+             "direction", "nt_first", "fold_max", "nt_store", "scalar_io")
 
 
 class SoftmaxTpError(RuntimeError):

@@ -27,6 +27,7 @@ struct Tuning {
     int64_t nt_first = 0;
     int64_t fold_max = 0;
     int64_t nt_store = 0;
+    int64_t scalar_io = 0;
 };
 // Written by softmax_tp_tune only; every reader takes a copy under the lock, so a sweep thread
 // that retunes while another thread plans or launches is not a data race (the call then sees
@@ -79,6 +80,14 @@ constexpr int64_t kOnchipQuadRowMaxVecs = 64;
 constexpr int64_t kOnchipTinyRowMaxVecs = 8;
 constexpr int kQuad = 16;
 constexpr int kTiny = 4;
+constexpr int kSolo = 1;
+// Rows of at most this many elements [fp32, 16-bit] get a single lane each (shape.block 1), 256
+// rows per workgroup: nothing to reduce across lanes and no lane idle.  With whole vectors if
+// every row starts on a 16-byte boundary (fp32 rows of 4 or 8 elements, 16-bit rows of 8 or 16),
+// element by element otherwise.  2^26 elements: fp32 rows of 4 0.280 -> 0.098 ms, of 5 0.341 ->
+// 0.128, of 8 0.155 -> 0.108; bf16 rows of 4 0.226 -> 0.075, of 8 0.181 -> 0.063, of 10 0.228 ->
+// 0.096, of 16 0.097 -> 0.065.  Longer rows lose: every lane then walks its own cache lines.
+constexpr int64_t kSoloRowMaxElems[2] = {9, 16};
 
 // Workgroup size and loads in flight on the rows path, by row length in 16-byte vectors.  From
 // round-robin sweeps of every shape over rows of 1.5 K to 128 K elements: a lane should see two
@@ -105,13 +114,20 @@ static const RowStep kRowSteps[2][3][5] = {
 };
 
 // algo: 0 Two-Pass, 1 Three-Pass with recomputation, 2 Three-Pass with reloading
-static void rows_shape(const Tuning &g_tune, int64_t rows, int64_t nvec, int elem_bytes, int algo,
-                       softmax_tp_shape_t *s)
+static void rows_shape(const Tuning &g_tune, int64_t rows, int64_t n, int V, int elem_bytes,
+                       int algo, softmax_tp_shape_t *s)
 {
+    const int64_t nvec = (n + V - 1) / V;
     s->chunk_vecs = 0;
     s->chunks = 1;
-    const bool group_forced = g_tune.block_rows == kTiny || g_tune.block_rows == kQuad ||
-                              g_tune.block_rows == kWave;
+    if (n <= kSoloRowMaxElems[elem_bytes == 4 ? 0 : 1] && !g_tune.block_rows && !g_tune.unroll_rows &&
+        (V == 1 || n % V == 0) && rows <= kThreadsMax) {
+        s->block = kSolo;  // with vectors: one or two; element-wise: two at a time up to 3, else four
+        s->unroll = V > 1 ? (int32_t)(n / V) : n <= 3 ? 2 : 4;
+        return;
+    }
+    const bool group_forced = g_tune.block_rows == kSolo || g_tune.block_rows == kTiny ||
+                              g_tune.block_rows == kQuad || g_tune.block_rows == kWave;
     if (group_forced || (nvec <= kWaveRowMaxVecs[elem_bytes == 4 ? 0 : 1][algo] && !g_tune.block_rows)) {
         // short rows: a group of 4, 16 or 64 lanes per row, several rows per workgroup
         const int wide = elem_bytes == 4 ? 0 : 1;
@@ -121,8 +137,8 @@ static void rows_shape(const Tuning &g_tune, int64_t rows, int64_t nvec, int ele
         int lanes = nvec <= kTinyRowMaxVecs[wide] ? kTiny : nvec <= quad_max ? kQuad : kWave;
         if (group_forced) lanes = (int)g_tune.block_rows;
         // a launch holds fewer than 2^32 threads: very many rows make do with fewer lanes each
-        while (lanes > kTiny && rows > kThreadsMax / lanes)
-            lanes = lanes == kWave ? kQuad : kTiny;
+        while (lanes > kSolo && rows > kThreadsMax / lanes)
+            lanes = lanes == kWave ? kQuad : lanes == kQuad ? kTiny : kSolo;
         int64_t rounds = (nvec + lanes - 1) / lanes;
         s->block = lanes;
         s->unroll = g_tune.unroll_rows ? (int32_t)g_tune.unroll_rows : rounds >= 4 ? 4 : (int32_t)rounds;
@@ -181,9 +197,13 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
     const Tuning g_tune = tuning();
     if (n > INT64_MAX / elem_bytes / rows)
         return TP_ERR_TOO_LARGE;
-    const int V = congruent16 ? 16 / elem_bytes : 1;
-    const int64_t nvec = (n + V - 1) / V;  // upper bound on the full vectors of a row
     const int64_t row_bytes = n * elem_bytes;
+    // (rows short enough for a lane of their own are read in vectors only if each of them can
+    // start on a 16-byte boundary; whether the first one does is the caller's to say)
+    const bool solo_ragged = n <= kSoloRowMaxElems[elem_bytes == 4 ? 0 : 1] && row_bytes % 16 != 0 &&
+                             force_path != 2 && g_tune.path != 2;  // (a rows-path matter)
+    const int V = congruent16 && !solo_ragged ? 16 / elem_bytes : 1;
+    const int64_t nvec = (n + V - 1) / V;  // upper bound on the full vectors of a row
     p->vector_elems = V;
 
     bool rows_path = row_bytes <= kRowsPathMaxBytes &&
@@ -196,15 +216,16 @@ static int make_plan(int64_t rows, int64_t n, int elem_bytes, bool congruent16, 
         if (rows > kGridMax || nvec > kChunkVecsMax)
             return TP_ERR_TOO_LARGE;
         p->path = 1;
-        rows_shape(g_tune, rows, nvec, elem_bytes, 0, &p->rows);
-        rows_shape(g_tune, rows, nvec, elem_bytes, 1, &p->rows_recompute);
-        rows_shape(g_tune, rows, nvec, elem_bytes, 2, &p->rows_reload);
+        rows_shape(g_tune, rows, n, V, elem_bytes, 0, &p->rows);
+        rows_shape(g_tune, rows, n, V, elem_bytes, 1, &p->rows_recompute);
+        rows_shape(g_tune, rows, n, V, elem_bytes, 2, &p->rows_reload);
         p->launches = 1;
         for (const softmax_tp_shape_t *sh : {&p->rows, &p->rows_recompute, &p->rows_reload}) {
             // block threads per row, whether that is a workgroup, a wave or a few lanes
             if (rows > kThreadsMax / sh->block)
                 return TP_ERR_TOO_LARGE;
-            const bool group = sh->block == kWave || sh->block == kQuad || sh->block == kTiny;
+            const bool group = sh->block == kWave || sh->block == kQuad || sh->block == kTiny ||
+                               sh->block == kSolo;
             if (!(group ? sh->unroll >= 1 && sh->unroll <= 4
                         : valid_block(sh->block) && valid_unroll(sh->unroll, elem_bytes)))
                 return TP_ERR_TUNING;
@@ -411,7 +432,7 @@ static int run_rows(Algo algo, const softmax_tp_plan_t &plan, const typename IO:
     const softmax_tp_shape_t &shape = algo == kTwoPass     ? plan.rows
                                       : algo == kRecompute ? plan.rows_recompute
                                                            : plan.rows_reload;
-    if (shape.block == kWave || shape.block == kQuad || shape.block == kTiny) {
+    if (shape.block == kWave || shape.block == kQuad || shape.block == kTiny || shape.block == kSolo) {
         // short rows: a lane group per row
         const int64_t per_group = kShortBlock / shape.block;
         const dim3 wgrid((uint32_t)((rows + per_group - 1) / per_group));
@@ -434,6 +455,7 @@ static int run_rows(Algo algo, const softmax_tp_plan_t &plan, const typename IO:
         };
         switch (shape.block * 8 + shape.unroll) {
 #define TP_GROUP(L, UU) case L * 8 + UU: return go(ic<L>{}, ic<UU>{});
+            TP_GROUP(kSolo, 1) TP_GROUP(kSolo, 2) TP_GROUP(kSolo, 3) TP_GROUP(kSolo, 4)
             TP_GROUP(kTiny, 1) TP_GROUP(kTiny, 2) TP_GROUP(kTiny, 3) TP_GROUP(kTiny, 4)
             TP_GROUP(kQuad, 1) TP_GROUP(kQuad, 2) TP_GROUP(kQuad, 3) TP_GROUP(kQuad, 4)
             TP_GROUP(kWave, 1) TP_GROUP(kWave, 2) TP_GROUP(kWave, 3) TP_GROUP(kWave, 4)
@@ -700,8 +722,6 @@ static int run_onchip(int algo, const typename IO::elem *x, typename IO::elem *y
     const int64_t hi = (n + V - 1) / V;
     hipStream_t st = (hipStream_t)stream;
     if (hi <= kOnchipWaveRowMaxVecs) {  // short rows: a lane group per row, as on the rows path
-        if (rows > kThreadsMax / kWave)
-            return TP_ERR_TOO_LARGE;
         const Tuning t = tuning();
         int lanes = hi <= kOnchipTinyRowMaxVecs ? kTiny : hi <= kOnchipQuadRowMaxVecs ? kQuad : kWave;
         if (t.block_rows == kTiny || t.block_rows == kQuad || t.block_rows == kWave)
@@ -709,6 +729,8 @@ static int run_onchip(int algo, const typename IO::elem *x, typename IO::elem *y
         const int64_t u = (hi + lanes - 1) / lanes;
         if (u > 4)
             return TP_ERR_TUNING;
+        if (rows > kThreadsMax / lanes)
+            return TP_ERR_TOO_LARGE;
         const int64_t per_group = kShortBlock / lanes;
         const dim3 wgrid((uint32_t)((rows + per_group - 1) / per_group)), wblock(kShortBlock);
         const bool y_nt = group_store_hint(lanes, n, es, true);
@@ -758,6 +780,15 @@ static int run_onchip(int algo, const typename IO::elem *x, typename IO::elem *y
 #undef TP_OC
 }
 
+// Whether a call reads and writes 16-byte vectors: x and y congruent modulo 16 bytes, and,
+// for rows short enough to get a lane of their own, every row starting on a 16-byte boundary.
+static bool vector_access(const void *x, const void *y, int64_t n, int elem_bytes)
+{
+    const bool solo = n <= kSoloRowMaxElems[elem_bytes == 4 ? 0 : 1];
+    const bool rows_aligned = (uintptr_t)x % 16 == 0 && (n * elem_bytes) % 16 == 0;
+    return congruent16(x, y) && tuning().scalar_io != 1 && (!solo || rows_aligned);
+}
+
 template <class IOV, class IOS>
 static int softmax_any(Algo algo, const typename IOV::elem *x, typename IOV::elem *y,
                        int64_t rows, int64_t n, void *stream)
@@ -766,7 +797,7 @@ static int softmax_any(Algo algo, const typename IOV::elem *x, typename IOV::ele
     int rc = check_args(x, y, rows, n, es);
     if (rc != TP_OK || rows == 0 || n == 0)
         return rc;
-    const bool vec = congruent16(x, y);
+    const bool vec = vector_access(x, y, n, es);
     softmax_tp_plan_t plan;
     rc = make_plan(rows, n, es, vec, 0, &plan);
     if (rc != TP_OK)
@@ -780,6 +811,27 @@ static int softmax_any(Algo algo, const typename IOV::elem *x, typename IOV::ele
                    : run_chunks_2p<IOS>(plan, x, y, rows, n, st);
     return vec ? run_chunks_3p<IOV>(algo, plan, x, y, rows, n, st)
                : run_chunks_3p<IOS>(algo, plan, x, y, rows, n, st);
+}
+
+// The on-chip entry points.  Rows short enough for a lane of their own go through the lane-per-row
+// kernels of the entry points above (Two-Pass, or Three-Pass with recomputation): a lane holds
+// its row in a few cache lines that it has just read itself, so x still comes from memory
+// once, and no group of lanes would be busy holding so little.
+template <class IOV, class IOS>
+static int onchip_any(int algo, const typename IOV::elem *x, typename IOV::elem *y, int64_t rows,
+                      int64_t n, void *stream)
+{
+    constexpr int es = (int)sizeof(typename IOV::elem);
+    if (n > 0 && rows > 0 && n <= kSoloRowMaxElems[es == 4 ? 0 : 1]) {
+        const int rc = check_args(x, y, rows, n, es);
+        if (rc != TP_OK)
+            return rc;
+        if (!congruent16(x, y))
+            return TP_ERR_ALIGN;
+        return softmax_any<IOV, IOS>(algo == kOnchipTwoPass ? kTwoPass : kRecompute, x, y, rows, n,
+                                     stream);
+    }
+    return run_onchip<IOV>(algo, x, y, rows, n, stream);
 }
 
 }  // namespace tp
@@ -841,32 +893,32 @@ int softmax3p_reload_f16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t
 
 int softmax2p_onchip_f32(const float *x, float *y, int64_t rows, int64_t n, void *stream)
 {
-    return run_onchip<F32x4>(kOnchipTwoPass, x, y, rows, n, stream);
+    return onchip_any<F32x4, F32x1>(kOnchipTwoPass, x, y, rows, n, stream);
 }
 
 int softmax2p_onchip_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n, void *stream)
 {
-    return run_onchip<BF16x8>(kOnchipTwoPass, x, y, rows, n, stream);
+    return onchip_any<BF16x8, BF16x1>(kOnchipTwoPass, x, y, rows, n, stream);
 }
 
 int softmax2p_onchip_f16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n, void *stream)
 {
-    return run_onchip<F16x8>(kOnchipTwoPass, x, y, rows, n, stream);
+    return onchip_any<F16x8, F16x1>(kOnchipTwoPass, x, y, rows, n, stream);
 }
 
 int softmax3p_onchip_f16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n, void *stream)
 {
-    return run_onchip<F16x8>(kOnchipThreePass, x, y, rows, n, stream);
+    return onchip_any<F16x8, F16x1>(kOnchipThreePass, x, y, rows, n, stream);
 }
 
 int softmax3p_onchip_f32(const float *x, float *y, int64_t rows, int64_t n, void *stream)
 {
-    return run_onchip<F32x4>(kOnchipThreePass, x, y, rows, n, stream);
+    return onchip_any<F32x4, F32x1>(kOnchipThreePass, x, y, rows, n, stream);
 }
 
 int softmax3p_onchip_bf16io(const uint16_t *x, uint16_t *y, int64_t rows, int64_t n, void *stream)
 {
-    return run_onchip<BF16x8>(kOnchipThreePass, x, y, rows, n, stream);
+    return onchip_any<BF16x8, BF16x1>(kOnchipThreePass, x, y, rows, n, stream);
 }
 
 static int run_extexp(bool hw, const float *x, float *m, float *e, int64_t count, void *stream)
@@ -1056,7 +1108,7 @@ int softmax2p_f32_static(const float *x, float *y, int64_t rows, int64_t n, void
     int rc = check_args(x, y, rows, n, 4);
     if (rc != TP_OK || rows == 0 || n == 0)
         return rc;
-    const bool vec = congruent16(x, y);
+    const bool vec = vector_access(x, y, n, 4);
     softmax_tp_plan_t plan;
     if ((rc = make_plan(rows, n, 4, vec, 0, &plan)) != TP_OK)
         return rc;
@@ -1109,6 +1161,7 @@ int softmax_tp_tune(const char *key, int64_t value)
         {"nt_first", &g_tune_shared.nt_first, kThree},
         {"fold_max", &g_tune_shared.fold_max, kAny},
         {"nt_store", &g_tune_shared.nt_store, kThree},
+        {"scalar_io", &g_tune_shared.scalar_io, kThree},
     };
     std::lock_guard<std::mutex> lock(g_tune_mutex);
     for (auto &k : keys) {
@@ -1117,7 +1170,7 @@ int softmax_tp_tune(const char *key, int64_t value)
         if (value != 0) {
             const bool rows_key = k.slot == &g_tune_shared.block_rows || k.slot == &g_tune_shared.unroll_rows;
             if (k.kind == kBlock && !valid_block(value) &&
-                !(rows_key && (value == kTiny || value == kQuad || value == kWave)))
+                !(rows_key && (value == kSolo || value == kTiny || value == kQuad || value == kWave)))
                 return TP_ERR_TUNING;
             if (k.kind == kUnroll && !valid_unroll(value, 4) && !(rows_key && value == 3))
                 return TP_ERR_TUNING;

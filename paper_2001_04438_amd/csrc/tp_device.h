@@ -138,8 +138,10 @@ __device__ __forceinline__ void wave_pair(float &m, float &n)
 template <int LANES>
 __device__ __forceinline__ float lanes_max(float v)
 {
-    static_assert(LANES == 64 || LANES == 16 || LANES == 4, "a wave, a row of 16 lanes or a quad");
-    if constexpr (LANES == 64) {
+    static_assert(LANES == 64 || LANES == 16 || LANES == 4 || LANES == 1, "a wave, a row of 16 lanes, a quad or a lane");
+    if constexpr (LANES == 1) {
+        return v;
+    } else if constexpr (LANES == 64) {
         return wave_max(v);
     } else {
         v = fmaxf(v, dpp<0xB1>(v));
@@ -155,8 +157,10 @@ __device__ __forceinline__ float lanes_max(float v)
 template <int LANES>
 __device__ __forceinline__ float lanes_sum(float v)
 {
-    static_assert(LANES == 64 || LANES == 16 || LANES == 4, "a wave, a row of 16 lanes or a quad");
-    if constexpr (LANES == 64) {
+    static_assert(LANES == 64 || LANES == 16 || LANES == 4 || LANES == 1, "a wave, a row of 16 lanes, a quad or a lane");
+    if constexpr (LANES == 1) {
+        return v;
+    } else if constexpr (LANES == 64) {
         return wave_sum(v);
     } else {
         v += dpp<0xB1>(v);

@@ -216,15 +216,16 @@ def test_short_rows_one_lane_group_each(gpu, oracle_mod, name, tol):
     64 vectors (16-bit: 128) 16 lanes each (16 rows per workgroup), up to 256 vectors a wave each (4 rows
     per workgroup): every unroll of each, row counts that leave groups idle."""
     rng = np.random.default_rng(83)
-    for rows, n, lanes in ((1001, 100, 16), (4097, 256, 16), (3000, 33, 4), (50, 1, 4), (17, 64, 16),
-                           (1, 129, 16), (33, 7, 4), (260, 255, 16), (5000, 16, 4), (777, 61, 16), (65, 65, 16),
+    for rows, n, lanes in ((1001, 100, 16), (4097, 256, 16), (3000, 33, 4), (50, 1, 1), (17, 64, 16),
+                           (1, 129, 16), (33, 7, 1), (260, 255, 16), (5000, 16, 4), (777, 61, 16), (65, 65, 16),
+                           (70001, 4, 1), (9999, 8, 1), (257, 9, 1), (300, 2, 1), (1025, 5, 1), (4000, 10, 4),
                            (901, 48, 4), (333, 45, 4), (444, 92, 16), (555, 380, 64), (99, 190, 16),
                            (6, 1024, 64), (513, 1021, 64), (1003, 257, 64), (5, 600, 64), (1234, 768, 64),
                            (700, 1300, 64), (301, 1405, 64), (299, 1409, 256)):   # a second round of the wave
         assert gpu.softmax_tp_plan(rows, n).rows.block == lanes
         x = rng.normal(0, 5, size=(rows, n)).astype(np.float32)
         _check(oracle_mod, x, _run(getattr(gpu, name), x), tol)
-    for n in (50, 255, 1001):      # unaligned rows: up to six edge elements, more than a quad has lanes
+    for n in (3, 4, 8, 9, 50, 255, 1001):   # unaligned rows: a lane per row element by element; up to six edge elements
         x = rng.normal(0, 5, size=(333, n)).astype(np.float32)
         _check(oracle_mod, x, _run(getattr(gpu, name), x, x_off=1, y_off=1), tol)
         _check(oracle_mod, x, _run(getattr(gpu, name), x, x_off=1, y_off=2), tol)   # element-wise format
@@ -272,13 +273,18 @@ def test_short_rows_one_wave_each_bf16(gpu, oracle_mod):
     for name in ("softmax2p_bf16io", "softmax3p_recompute_bf16io", "softmax3p_reload_bf16io"):
         for rows, n in ((1001, 100), (4097, 512), (7, 2048), (513, 2041), (300, 513), (9, 8), (2000, 37),
                         (1500, 96), (700, 192), (600, 768), (450, 1000), (350, 1536), (3333, 48),
-                        (500, 3000), (257, 4090), (255, 4100)):
-            assert gpu.softmax_tp_plan(rows, n, 2).rows.block == (4 if n <= 128 else 16 if n <= 1024 else
-                                                                  64 if n <= 4096 else 256)
+                        (500, 3000), (257, 4090), (255, 4100), (30001, 4), (777, 16), (555, 11), (444, 15), (3, 1)):
+            assert gpu.softmax_tp_plan(rows, n, 2).rows.block == (1 if n <= 16 else 4 if n <= 128 else 16 if n <= 1024
+                                                                  else 64 if n <= 4096 else 256)
             x = workloads.f32_to_bf16_bits(rng.normal(0, 5, size=(rows, n)).astype(np.float32)).reshape(rows, n)
             _check(oracle_mod, x, _run(getattr(gpu, name), x), TOL_BF16, bf16=True)
         x = workloads.cfg5(rows=77, n=1003)
         _check(oracle_mod, x, _run(getattr(gpu, name), x, x_off=3, y_off=3), TOL_BF16, bf16=True)
+        for n in (4, 8, 13, 16):     # a lane per row: vectors only when every row starts on 16 bytes
+            x = workloads.f32_to_bf16_bits(rng.normal(0, 5, size=(2001, n)).astype(np.float32)).reshape(2001, n)
+            for off, yoff in ((1, 1), (8, 8), (4, 4), (0, 3)):
+                _check(oracle_mod, x, _run(getattr(gpu, name), x, x_off=off, y_off=yoff), TOL_BF16, bf16=True)
+            _check(oracle_mod, x, _run(getattr(gpu, name), x, inplace=True), TOL_BF16, bf16=True)
 
 
 @pytest.mark.parametrize("name,tol", ALGOS_F32)

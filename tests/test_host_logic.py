@@ -170,6 +170,19 @@ def test_planner_covers_odd_shapes(B):
                 nvec = -(-n // V)
                 for shape in (p.reduce, p.map, p.mapsum):
                     assert shape.chunks * shape.chunk_vecs >= nvec
+    # rows of a few elements: one lane each; vectors only where every row can start on a 16-byte boundary
+    for s, most, V in ((4, 9, 4), (2, 16, 8)):
+        for n in range(1, most + 3):
+            p = B.softmax_tp_plan(100_000, n, s)
+            if n > most:
+                assert p.rows.block == 4 and p.vector_elems == V
+            elif n % V == 0:
+                assert (p.rows.block, p.rows.unroll, p.vector_elems) == (1, n // V, V)
+            else:
+                assert (p.rows.block, p.rows.unroll, p.vector_elems) == (1, 2 if n <= 3 else 4, 1)
+            assert p.rows_recompute.block == p.rows.block and p.rows_reload.block == p.rows.block
+            q = B.softmax_tp_plan(100_000, n, s, False)
+            assert q.vector_elems == 1 and (q.rows.block == 1 if n <= most else q.rows.block in (4, 16))
     assert B.softmax_tp_plan(0, 5).path == 0 and B.softmax_tp_plan(5, 0).path == 0
     big = B.softmax_tp_plan(1, 1 << 40)
     assert big.path == 2 and big.map.chunks * big.map.chunk_vecs >= (1 << 38)
@@ -177,7 +190,8 @@ def test_planner_covers_odd_shapes(B):
     assert big.map.chunks * big.map.block < 2 ** 32 and big.map.chunk_vecs > 2048
     assert B.softmax_tp_plan(1 << 29, 64).rows.block == 4       # 2^31 threads: still one launch
     assert B.softmax_tp_plan(1 << 27, 300).rows.block == 16     # a wave each would be 2^33 threads
-    for rows, n in ((1 << 23, 8192), (1, 1 << 60), (1 << 31, 64), (1 << 30, 300)):
+    assert B.softmax_tp_plan(1 << 30, 300).rows.block == 1      # ... and 16 or 4 lanes each too many
+    for rows, n in ((1 << 23, 8192), (1, 1 << 60), (1 << 31, 64), (1 << 33, 8)):
         with pytest.raises(B.SoftmaxTpError) as e:
             B.softmax_tp_plan(rows, n)
         assert e.value.code == B.TP_ERR_TOO_LARGE
