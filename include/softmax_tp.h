@@ -271,6 +271,7 @@ TP_API int softmax_tp_plan(int64_t rows, int64_t n, int32_t elem_bytes, int32_t 
  *                     hint, 2 with it; default: without it for rows under 1 KiB (on-chip entry
  *                     points: under 128 bytes) whose length neither divides nor is a multiple
  *                     of 128 bytes, so that neighbouring rows share cache lines unevenly
+ *   "scalar_io"       1: element-wise accesses even where x and y would allow 16-byte vectors
  * block is 256, 512 or 1024; unroll 2, 4 or 8 (16-bit formats: 2 or 4); in addition the
  * pair block 128, unroll 1.  "block_rows" also takes 1, 4, 16 or 64: a group of that many lanes
  * per row, several rows per workgroup (what rows of at most 256 vectors get by default), with
