@@ -527,11 +527,21 @@ __device__ __forceinline__ void stream(const Seg<IO> &s, P &p, uint32_t tid = th
     vec *yb = s.yv + s.vb;
     const uint32_t cnt = s.cnt;
     uint32_t k = tid;
-    // Full rounds as long as every lane of the wave has one: a wave whose lanes disagree would run
-    // this loop body for some and the partly filled round below for the others, one after the
-    // other.  When the vote fails a lane has at most U vectors left (the lanes of a wave are in
-    // the same round, and rows that share a wave differ by at most one vector).
-    for (; wave_all(k + (uint32_t)((U - 1) * BLOCK) < cnt); k += (uint32_t)(U * BLOCK)) {
+    // Lane groups (BLOCK <= 64, several rows per wave): full rounds as long as every lane of the
+    // wave has one.  A wave whose lanes disagree would run this loop body for some and the partly
+    // filled round below for the others, one after the other, and with a few rounds per row that
+    // is most of the time.  When the vote fails a lane has at most U vectors left (the lanes of a
+    // wave are in the same round, and rows that share a wave differ by at most one vector).
+    // Workgroups decide per lane: only the wave that holds the end of the row ever disagrees, and
+    // the vote in the loop cost the arithmetic-heavy read-only passes 2 %.
+    auto full_round = [&](uint32_t at) {
+        const bool mine = at + (uint32_t)((U - 1) * BLOCK) < cnt;
+        if constexpr (BLOCK <= 64)
+            return wave_all(mine);
+        else
+            return mine;
+    };
+    for (; full_round(k); k += (uint32_t)(U * BLOCK)) {
         vec v[U];
 #pragma unroll
         for (int u = 0; u < U; ++u)
